@@ -1,0 +1,203 @@
+/*
+ * grace_moe.h - C ABI of the MI355X (gfx950) GRACE-MoE layer hot path.
+ *
+ * One GPU's share of one Mixture-of-Experts layer as reorganised by GRACE-MoE
+ * (arxiv 2509.25041): top-k gating, locality-aware replica selection against an
+ * expert placement / replica table, the node-then-GPU dispatch permutation, the
+ * grouped SwiGLU expert FFN over the rows routed to this GPU, and the weighted
+ * combine back to token order.
+ *
+ * Conventions
+ *  - Every function returns a status: GRACE_OK (0) or a negative error code.
+ *    Nothing throws, aborts or prints.  grace_last_error() gives the text of the
+ *    calling thread's most recent failure.
+ *  - Pointers marked HOST are read during the call and not retained.
+ *    Pointers marked DEVICE belong to the caller; the library borrows them until
+ *    the work it enqueued on `stream` has completed.  Compute calls are
+ *    asynchronous on `stream` (a hipStream_t passed as void*; NULL = the default
+ *    stream) and never synchronise the device.
+ *  - Shapes and ranges are checked on the host before anything is launched.
+ *    Values held in device memory (logits, ids) are the caller's precondition:
+ *    logits must be finite, ids in range.  Out-of-range ids never cause an
+ *    out-of-bounds access; the affected outputs are unspecified.
+ *  - All matrices are dense row-major.  Index arrays are int32.
+ *  - Assignment index a = t*k + j (token t, j-th chosen expert).
+ *  - An "instance" is one copy of an expert on one rank.  Instance ids are
+ *    positions in the dispatch order: all instances sorted by
+ *    (node of rank, rank, expert id).  The instances of one rank are therefore
+ *    consecutive ids; the position of an instance among its rank's instances is
+ *    its "slot", which is also the index of its weights in the stacked weight
+ *    arrays passed to grace_expert_ffn.
+ */
+#ifndef GRACE_MOE_H
+#define GRACE_MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    GRACE_OK = 0,
+    GRACE_EINVAL = -1, /* null pointer, negative size, value out of range           */
+    GRACE_ESHAPE = -2, /* shape not supported (limits below) or not matching table */
+    GRACE_ETABLE = -3, /* malformed placement table                                 */
+    GRACE_ENOMEM = -4, /* host or device allocation failed                          */
+    GRACE_EHIP = -5    /* HIP runtime error (text in grace_last_error)              */
+};
+
+typedef enum { GRACE_F32 = 0, GRACE_BF16 = 1 } grace_dtype;
+
+/* Limits checked by the entry points. */
+#define GRACE_MAX_EXPERTS 256   /* E                        */
+#define GRACE_MAX_TOPK 64       /* k                        */
+#define GRACE_MAX_RANKS 1024    /* R                        */
+#define GRACE_MAX_INSTANCES 4096 /* I                       */
+#define GRACE_MAX_POLL_WEIGHT 65535u
+
+typedef struct grace_table grace_table; /* opaque; owns host and device copies */
+
+/* ---- placement / replica table (Sections 4.1-4.3 of the paper) -------------
+ * The output of the paper's offline phase, given purely as data: the virtual
+ * topology (rank -> node), the per-GPU polling weights of the weighted
+ * round-robin (Section 4.3, Algorithm 3: map gpu_id -> weight) and, in CSR form
+ * over experts, the ranks holding an instance of each expert (primary group
+ * member or replica; Section 4.2 - the routing treats all instances alike).
+ *
+ * All pointers HOST.
+ *   E, R, N      experts, ranks (virtual GPUs), nodes
+ *   rank_node    [R]   node of each rank, values in [0, N), non-decreasing
+ *   poll_weight  [R]   integer polling weight, 1 .. GRACE_MAX_POLL_WEIGHT
+ *   inst_ptr     [E+1] instances of expert e are inst_rank[inst_ptr[e] .. inst_ptr[e+1])
+ *   inst_rank    [I]   hosting rank, strictly ascending within one expert
+ * Errors: GRACE_EINVAL (null, sizes < 1), GRACE_ESHAPE (over the limits),
+ * GRACE_ETABLE (expert without instance, rank out of range, duplicate or
+ * unsorted (expert, rank), zero or oversized weight, decreasing rank_node,
+ * node id out of range, inst_ptr not starting at 0 or decreasing).
+ */
+int grace_table_validate(int32_t E, int32_t R, int32_t N, const int32_t *rank_node,
+                         const uint32_t *poll_weight, const int32_t *inst_ptr, const int32_t *inst_rank);
+
+/* Validates as above, then builds the table on the current HIP device
+ * (device copy made on `stream`, complete on return).  *out is set only on
+ * success and must be released with grace_table_destroy. */
+int grace_table_create(grace_table **out, int32_t E, int32_t R, int32_t N, const int32_t *rank_node,
+                       const uint32_t *poll_weight, const int32_t *inst_ptr, const int32_t *inst_rank,
+                       void *stream);
+int grace_table_destroy(grace_table *table); /* NULL is accepted */
+
+/* Sizes of a table.  Any output pointer may be NULL. */
+int grace_table_info(const grace_table *table, int32_t *E, int32_t *R, int32_t *N, int32_t *I,
+                     int32_t *max_local_slots);
+
+/* The dispatch order (Section 5: first by target node, then by target GPU).
+ * HOST outputs, any may be NULL: inst_expert [I], inst_rank [I] for each
+ * instance id; rank_ptr [R+1]: the instances of rank r are ids
+ * rank_ptr[r] .. rank_ptr[r+1]. */
+int grace_table_instances(const grace_table *table, int32_t *inst_expert, int32_t *inst_rank, int32_t *rank_ptr);
+
+/* Experts hosted by `rank` in slot order (ascending expert id): tells the
+ * caller how to stack the weights for grace_expert_ffn.  HOST outputs;
+ * experts_out must hold max_local_slots entries. */
+int grace_table_local_experts(const grace_table *table, int32_t rank, int32_t *experts_out, int32_t *n_out);
+
+/* Bytes of device scratch that any single call below needs for these sizes
+ * (the same buffer may be reused by consecutive calls on one stream).
+ * f and n_shared may be 0 when the FFN entry points are not used.  Returns 0
+ * on invalid arguments.  The buffer must be 256-byte aligned. */
+size_t grace_workspace_bytes(int32_t T, int32_t E, int32_t k, int32_t I, int32_t d, int32_t f, int32_t n_shared,
+                             grace_dtype dt);
+
+/* ---- grace_route: top-k gating + replica pick -------------------------------
+ * Gating (Section 3: every token activates k experts): the k largest logits of
+ * a token, in descending order, equal logits to the lower expert id; gate
+ * weight = softmax over all E logits, divided by the sum over the k chosen when
+ * renorm != 0.
+ * Replica pick (Section 4.3; Algorithm 4 with Algorithm 3 inside a tier): all
+ * T tokens reside on local_rank.  For each assignment, in order of a, the c-th
+ * request for expert e (c starts at rr_in[e]) goes to
+ *   the instance on local_rank, if there is one; else
+ *   among the instances on local_rank's node, if any; else among all instances,
+ * the candidate (ascending rank) whose cumulative polling-weight interval
+ * contains c mod W, W = sum of the tier's polling weights (deterministic
+ * weighted round-robin: over any W consecutive requests each candidate receives
+ * exactly its weight).
+ *
+ * DEVICE: logits [T,E] fp32; rr_in [E] or NULL (= zeros); rr_out [E] or NULL,
+ * receives (rr_in[e] + requests of e) mod W_e; topk_expert [T,k];
+ * topk_weight [T,k] fp32; topk_inst [T,k] instance ids; expert_count [E]
+ * requests per expert in this call; ws from grace_workspace_bytes.
+ * Limits: 1 <= k <= min(E, GRACE_MAX_TOPK), E == table's E, T*k < 2^31, T >= 0.
+ */
+int grace_route(const grace_table *table, int32_t local_rank, const float *logits, int32_t T, int32_t E, int32_t k,
+                int32_t renorm, const uint32_t *rr_in, uint32_t *rr_out, int32_t *topk_expert, float *topk_weight,
+                int32_t *topk_inst, int32_t *expert_count, void *ws, void *stream);
+
+/* ---- grace_permute: hierarchical dispatch permutation -----------------------
+ * Orders the T*k assignments by instance id, i.e. by (node, rank, slot) - the
+ * order in which the two-stage dispatch of Section 5 forwards rows first to the
+ * target node and then to the target GPU - keeping assignment order among equal
+ * ids (a stable sort), and moves the token rows into that order.
+ *
+ * DEVICE: topk_inst [T*k]; x [T,d] rows of dtype dt, or NULL to build only the
+ * index arrays (then xp is ignored); outputs perm_pos [T*k] (assignment ->
+ * buffer position), perm_src [T*k] (buffer position -> assignment),
+ * inst_off [I+1], rank_off [R+1], node_off [N+1] (exclusive row offsets of each
+ * instance / rank / node; the last entry of each is T*k), xp [T*k,d] with
+ * xp[p] = x[perm_src[p] / k].
+ * Limits: d >= 1 and d * sizeof(dt) a multiple of 16 when x != NULL.
+ */
+int grace_permute(const grace_table *table, const int32_t *topk_inst, int32_t T, int32_t k, const void *x, int32_t d,
+                  grace_dtype dt, int32_t *perm_pos, int32_t *perm_src, int32_t *inst_off, int32_t *rank_off,
+                  int32_t *node_off, void *xp, void *ws, void *stream);
+
+/* ---- grace_expert_ffn: grouped SwiGLU FFN over one rank's rows ---------------
+ * The expert computation between dispatch and aggregation (Section 1).  For
+ * every instance i hosted by `rank` (slot s, expert e) and every buffer row p
+ * in [inst_off[i], inst_off[i+1]):
+ *     y[p] = W_down[s] ( silu(W_gate[s] xp[p]) * (W_up[s] xp[p]) ),
+ *     silu(g) = g / (1 + exp(-g)),
+ * with fp32 accumulation.  For GRACE_BF16 the hidden activation is rounded to
+ * bf16 before the down projection and y is stored in bf16; GRACE_F32 stays fp32
+ * end to end.  Rows of other ranks are not touched.
+ *
+ * DEVICE: xp [T*k,d]; inst_off [I+1] as written by grace_permute;
+ * w_gate, w_up [S,f,d] and w_down [S,d,f], S = number of local slots, slot
+ * order as given by grace_table_local_experts; every weight row holds one
+ * output feature, contiguous over the input feature; y [T*k,d].
+ * Limits: d and f multiples of 8 for GRACE_BF16.
+ * `rank` is an argument (normally local_rank) so that a caller can evaluate
+ * every virtual rank on one device.
+ */
+int grace_expert_ffn(const grace_table *table, int32_t rank, const void *xp, const int32_t *inst_off, int32_t T,
+                     int32_t k, int32_t d, int32_t f, grace_dtype dt, const void *w_gate, const void *w_up,
+                     const void *w_down, void *y, void *ws, void *stream);
+
+/* Always-on shared experts evaluated on all T token rows and summed:
+ *     y_shared[t] = sum_s W_down[s] ( silu(W_gate[s] x[t]) * (W_up[s] x[t]) ).
+ * DEVICE: x [T,d]; w_gate, w_up [n_shared,f,d]; w_down [n_shared,d,f];
+ * y_shared [T,d].  Same dtype rules and limits as grace_expert_ffn. */
+int grace_shared_ffn(const void *x, int32_t T, int32_t d, int32_t f, int32_t n_shared, grace_dtype dt,
+                     const void *w_gate, const void *w_up, const void *w_down, void *y_shared, void *ws,
+                     void *stream);
+
+/* ---- grace_combine: weighted aggregation back to token order ----------------
+ * The aggregation step that follows the expert computation (Section 1):
+ *     out[t] = sum_{j<k} topk_weight[t,j] * y[perm_pos[t*k+j]]  (+ y_shared[t]),
+ * accumulated in fp32 in ascending j and rounded once to dt.
+ * DEVICE: y [T*k,d]; perm_pos [T*k]; topk_weight [T,k]; y_shared [T,d] or NULL;
+ * out [T,d].  Limits: d * sizeof(dt) a multiple of 16.
+ */
+int grace_combine(const void *y, const int32_t *perm_pos, const float *topk_weight, int32_t T, int32_t k, int32_t d,
+                  grace_dtype dt, const void *y_shared, void *out, void *stream);
+
+/* Text of the calling thread's most recent error ("" if none).  The pointer
+ * stays valid until the thread's next failing call. */
+const char *grace_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRACE_MOE_H */

@@ -1,0 +1,26 @@
+"""MI355X-native GRACE-MoE layer hot path (arxiv 2509.25041).
+
+Thin Python binding over ``libgrace_moe.so`` (hand-written HIP kernels for
+gfx950 behind a C ABI, see ``include/grace_moe.h``).  The functions here carry
+the names of the C entry points and only marshal arguments: every step of the
+path runs in the library's kernels.  PyTorch provides device memory and
+streams, nothing else.  There is no CPU fallback: if the library cannot be
+loaded, importing the binding's functions raises.
+"""
+from .binding import (  # noqa: F401
+    GRACE_BF16,
+    GRACE_F32,
+    GraceError,
+    GraceTable,
+    grace_combine,
+    grace_expert_ffn,
+    grace_last_error,
+    grace_permute,
+    grace_route,
+    grace_shared_ffn,
+    grace_table_validate,
+    grace_workspace_bytes,
+    library_path,
+    load_library,
+)
+from .layer import GraceMoELayer  # noqa: F401

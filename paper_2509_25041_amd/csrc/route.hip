@@ -1,0 +1,196 @@
+// grace_route: top-k gating, per-expert request counter, locality-first replica pick.
+//
+// Three launches, all integer-exact and free of order-dependent atomics:
+//   1. topk_kernel   one wavefront per token: k rounds of wave-wide arg-max over
+//                    (logit desc, expert id asc), softmax weights, and a histogram
+//                    of the chosen experts per chunk of 64 tokens;
+//   2. route_scan    exclusive scan of the chunk histograms per expert -> the
+//                    number of earlier requests of each expert before each chunk
+//                    (the weighted round-robin counter of Section 4.3);
+//   3. pick_kernel   one wavefront per chunk walks its assignments in order, ranks
+//                    equal experts with ballot-based matching, and maps request
+//                    number c to the candidate of the tier Algorithm 4 selects
+//                    whose cumulative polling-weight interval holds c mod W.
+#include "common.h"
+#include "wave_utils.h"
+
+namespace grace {
+
+__device__ __forceinline__ uint32_t ordered_bits(float v) {
+    const uint32_t u = __float_as_uint(v);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float from_ordered_bits(uint32_t o) {
+    return __uint_as_float((o & 0x80000000u) ? (o ^ 0x80000000u) : ~o);
+}
+
+template <int VPL>
+__global__ __launch_bounds__(256) void topk_kernel(const float *__restrict__ logits, int T, int E, int k, int renorm,
+                                                   int32_t *__restrict__ topk_expert,
+                                                   float *__restrict__ topk_weight,
+                                                   int32_t *__restrict__ chunk_hist) {
+    __shared__ int32_t hist[GRACE_MAX_EXPERTS];
+    const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < E; i += 256) hist[i] = 0;
+    __syncthreads();
+    const int chunk = (int)blockIdx.x;
+    constexpr int TOK_PER_WAVE = ROUTE_TOKENS_PER_CHUNK / 4;
+    const int t_begin = chunk * ROUTE_TOKENS_PER_CHUNK + wave * TOK_PER_WAVE;
+    for (int i = 0; i < TOK_PER_WAVE; ++i) {
+        const int t = t_begin + i;
+        if (t >= T) break;  // uniform per wavefront
+        float val[VPL];
+        uint64_t key[VPL];
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) {
+            const int e = lane + 64 * v;
+            float x = (e < E) ? logits[(size_t)t * E + e] : -INFINITY;
+            if (x == 0.0f) x = 0.0f;  // -0.0 and +0.0 compare equal: make them the same bits
+            val[v] = x;
+            // larger key wins: value first, then the lower expert id
+            key[v] = ((uint64_t)ordered_bits(x) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)e);
+            if (e >= E) key[v] = 0;
+        }
+        int my_e = 0;
+        float my_l = 0.0f;
+        for (int j = 0; j < k; ++j) {
+            uint64_t best = 0;
+#pragma unroll
+            for (int v = 0; v < VPL; ++v) best = key[v] > best ? key[v] : best;
+            best = wave_max_u64(best);
+            const int e = (int)(0xFFFFFFFFu - (uint32_t)best);
+            if (lane == j) {
+                my_e = e;
+                my_l = from_ordered_bits((uint32_t)(best >> 32));
+            }
+#pragma unroll
+            for (int v = 0; v < VPL; ++v)
+                if (lane + 64 * v == e) key[v] = 0;  // taken
+        }
+        const float mx = __shfl(my_l, 0, 64);  // the first pick is the maximum logit
+        float part = 0.0f;
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) part += (lane + 64 * v < E) ? expf(val[v] - mx) : 0.0f;
+        const float den = wave_sum(part);
+        float w = (lane < k) ? expf(my_l - mx) / den : 0.0f;
+        if (renorm) {
+            const float s = wave_sum(w);
+            w = w / s;
+        }
+        if (lane < k) {
+            topk_expert[(size_t)t * k + lane] = my_e;
+            topk_weight[(size_t)t * k + lane] = w;
+            atomicAdd(&hist[my_e], 1);
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < E; i += 256) chunk_hist[(size_t)chunk * E + i] = hist[i];
+}
+
+__global__ __launch_bounds__(SCAN_THREADS) void route_scan_kernel(const int32_t *__restrict__ hist,
+                                                                  int32_t *__restrict__ base, int nchunks, int E,
+                                                                  const uint32_t *__restrict__ rr_in,
+                                                                  uint32_t *__restrict__ rr_out,
+                                                                  int32_t *__restrict__ expert_count,
+                                                                  const int32_t *__restrict__ cand_ptr,
+                                                                  const uint32_t *__restrict__ cand_cum) {
+    __shared__ int32_t totals[GRACE_MAX_EXPERTS];
+    __shared__ int32_t part_sums[SCAN_THREADS];
+    const int tid = (int)threadIdx.x;
+    for (int i = tid; i < E; i += SCAN_THREADS) totals[i] = 0;
+    __syncthreads();
+    block_scan_chunks(hist, base, nchunks, E, totals, part_sums);
+    __syncthreads();
+    for (int e = tid; e < E; e += SCAN_THREADS) {
+        const int32_t n = totals[e];
+        expert_count[e] = n;
+        if (rr_out) {
+            const uint32_t W = cand_cum[cand_ptr[e + 1] - 1];
+            const uint64_t c = (uint64_t)(rr_in ? rr_in[e] : 0u) + (uint64_t)(uint32_t)n;
+            rr_out[e] = (uint32_t)(c % W);
+        }
+    }
+}
+
+__global__ __launch_bounds__(64) void pick_kernel(const int32_t *__restrict__ topk_expert, int64_t n_assign, int E,
+                                                  int k, const int32_t *__restrict__ chunk_base,
+                                                  const uint32_t *__restrict__ rr_in,
+                                                  const int32_t *__restrict__ cand_ptr,
+                                                  const int32_t *__restrict__ cand_g,
+                                                  const uint32_t *__restrict__ cand_cum,
+                                                  int32_t *__restrict__ topk_inst, int nbits) {
+    __shared__ uint32_t cnt[GRACE_MAX_EXPERTS];
+    const int lane = (int)threadIdx.x;
+    const int chunk = (int)blockIdx.x;
+    for (int e = lane; e < E; e += 64) cnt[e] = (uint32_t)chunk_base[(size_t)chunk * E + e];
+    __syncthreads();
+    const int64_t a0 = (int64_t)chunk * ROUTE_TOKENS_PER_CHUNK * k;
+    const int64_t a1 = min(n_assign, a0 + (int64_t)ROUTE_TOKENS_PER_CHUNK * k);
+    const uint64_t lt = lanemask_lt();
+    for (int64_t b = a0; b < a1; b += 64) {
+        const int64_t a = b + lane;
+        bool valid = a < a1;
+        int e = valid ? topk_expert[a] : 0;
+        valid = valid && (unsigned)e < (unsigned)E;
+        const uint64_t same = wave_match((uint32_t)e, valid, nbits);
+        if (valid) {
+            const uint32_t rank = (uint32_t)__popcll(same & lt);
+            const uint64_t c = (uint64_t)cnt[e] + rank + (uint64_t)(rr_in ? rr_in[e] : 0u);
+            const int cb = cand_ptr[e], ce = cand_ptr[e + 1];
+            const uint32_t W = cand_cum[ce - 1];
+            const uint32_t q = (c >> 32) ? (uint32_t)(c % W) : ((uint32_t)c % W);
+            int s = cb;
+            while (s < ce - 1 && cand_cum[s] <= q) ++s;
+            topk_inst[a] = cand_g[s];
+        }
+        __syncthreads();
+        if (valid && is_last_of(same)) cnt[e] += (uint32_t)__popcll(same);
+        __syncthreads();
+    }
+}
+
+}  // namespace grace
+
+using namespace grace;
+
+extern "C" int grace_route(const grace_table *table, int32_t local_rank, const float *logits, int32_t T, int32_t E,
+                           int32_t k, int32_t renorm, const uint32_t *rr_in, uint32_t *rr_out, int32_t *topk_expert,
+                           float *topk_weight, int32_t *topk_inst, int32_t *expert_count, void *ws, void *stream) {
+    if (!table) return fail(GRACE_EINVAL, "route: table is null");
+    if (T < 0) return fail(GRACE_EINVAL, "route: T=%d is negative", T);
+    if (E != table->E) return fail(GRACE_ESHAPE, "route: E=%d but the table has %d experts", E, table->E);
+    if (k < 1 || k > E || k > GRACE_MAX_TOPK)
+        return fail(GRACE_EINVAL, "route: k=%d outside [1, min(E=%d, %d)]", k, E, GRACE_MAX_TOPK);
+    if (local_rank < 0 || local_rank >= table->R)
+        return fail(GRACE_EINVAL, "route: local_rank=%d outside [0,%d)", local_rank, table->R);
+    if ((int64_t)T * k > INT32_MAX) return fail(GRACE_ESHAPE, "route: T*k exceeds 2^31-1");
+    if (!expert_count || !ws) return fail(GRACE_EINVAL, "route: expert_count or ws is null");
+    if (T > 0 && (!logits || !topk_expert || !topk_weight || !topk_inst))
+        return fail(GRACE_EINVAL, "route: null device pointer");
+    hipStream_t st = (hipStream_t)stream;
+    const int nchunks = (int)ceil_div(T, ROUTE_TOKENS_PER_CHUNK);
+    int32_t *hist = (int32_t *)ws;
+    int32_t *base = (int32_t *)((char *)ws + align_up((size_t)nchunks * E * 4, 256));
+    const int32_t *cand_ptr = table->d_cand_ptr + (size_t)local_rank * E;
+    if (nchunks > 0) {
+        const int vpl = (E + 63) / 64;
+        switch (vpl) {
+            case 1: topk_kernel<1><<<nchunks, 256, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, hist); break;
+            case 2: topk_kernel<2><<<nchunks, 256, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, hist); break;
+            case 3: topk_kernel<3><<<nchunks, 256, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, hist); break;
+            default: topk_kernel<4><<<nchunks, 256, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, hist); break;
+        }
+        GRACE_LAUNCH_CHECK("topk_kernel");
+    }
+    route_scan_kernel<<<1, SCAN_THREADS, 0, st>>>(hist, base, nchunks, E, rr_in, rr_out, expert_count, cand_ptr,
+                                                  table->d_cand_cum);
+    GRACE_LAUNCH_CHECK("route_scan_kernel");
+    if (nchunks > 0) {
+        int nbits = 0;
+        while ((1 << nbits) < E) ++nbits;
+        pick_kernel<<<nchunks, 64, 0, st>>>(topk_expert, (int64_t)T * k, E, k, base, rr_in, cand_ptr, table->d_cand_g,
+                                            table->d_cand_cum, topk_inst, nbits);
+        GRACE_LAUNCH_CHECK("pick_kernel");
+    }
+    return GRACE_OK;
+}

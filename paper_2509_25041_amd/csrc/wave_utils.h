@@ -1,0 +1,92 @@
+// Wavefront-level (64 lanes) helpers used by the routing and permutation kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace grace {
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63u); }
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)v, o, 64);
+        uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)(v >> 32), o, 64);
+        uint64_t w = ((uint64_t)hi << 32) | lo;
+        v = w > v ? w : v;
+    }
+    return v;
+}
+
+// Lanes holding the same key as this lane (among lanes with valid == true).
+// nbits = number of significant key bits.  The result is meaningless for
+// lanes with valid == false.
+__device__ __forceinline__ uint64_t wave_match(uint32_t key, bool valid, int nbits) {
+    uint64_t m = __ballot(valid);
+    for (int b = 0; b < nbits; ++b) {
+        const bool bit = (key >> b) & 1u;
+        const uint64_t bal = __ballot(bit);
+        m &= bit ? bal : ~bal;
+    }
+    return m;
+}
+__device__ __forceinline__ uint64_t lanemask_lt() { return (1ull << lane_id()) - 1ull; }
+// true for the highest lane of a match set
+__device__ __forceinline__ bool is_last_of(uint64_t same) {
+    const int l = lane_id();
+    const uint64_t above = (l == 63) ? 0ull : (same >> (l + 1));
+    return above == 0ull;
+}
+__device__ __forceinline__ int bits_for(int nkeys) {
+    int b = 0;
+    while ((1 << b) < nkeys) ++b;
+    return b;
+}
+
+// Exclusive scan over chunks of a [nchunks][nkeys] histogram, per key:
+// base[c][key] = sum_{c' < c} hist[c'][key]; totals[key] = column sum (LDS or
+// global array of nkeys entries).  Must be called by a whole block of
+// SCAN_THREADS threads; `part_sums` is LDS of SCAN_PARTS * SCAN_KW ints.
+constexpr int SCAN_THREADS = 1024;
+constexpr int SCAN_KW = 64;
+constexpr int SCAN_PARTS = SCAN_THREADS / SCAN_KW;
+
+__device__ inline void block_scan_chunks(const int32_t *__restrict__ hist, int32_t *__restrict__ base, int nchunks,
+                                         int nkeys, int32_t *totals, int32_t *part_sums) {
+    const int tid = (int)threadIdx.x;
+    const int kl = tid % SCAN_KW, part = tid / SCAN_KW;
+    const int per = (nchunks + SCAN_PARTS - 1) / SCAN_PARTS;
+    const int c_lo = min(nchunks, part * per), c_hi = min(nchunks, c_lo + per);
+    for (int k0 = 0; k0 < nkeys; k0 += SCAN_KW) {
+        const int key = k0 + kl;
+        int32_t sum = 0;
+        if (key < nkeys)
+            for (int c = c_lo; c < c_hi; ++c) sum += hist[(size_t)c * nkeys + key];
+        part_sums[part * SCAN_KW + kl] = sum;
+        __syncthreads();
+        int32_t run = 0;
+        for (int p = 0; p < part; ++p) run += part_sums[p * SCAN_KW + kl];
+        if (key < nkeys) {
+            if (part == SCAN_PARTS - 1) totals[key] = run + sum;
+            for (int c = c_lo; c < c_hi; ++c) {
+                const size_t i = (size_t)c * nkeys + key;
+                base[i] = run;
+                run += hist[i];
+            }
+        }
+        __syncthreads();
+    }
+}
+
+}  // namespace grace

@@ -1,0 +1,330 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle on the same
+seeded inputs.  Integer outputs bit-exact; gate weights within 1e-6 relative;
+FFN / combine outputs within 2e-2 (bf16) / 1e-5 (fp32) by the metric
+max |y - r| / max(|r|, rms(r))."""
+from types import SimpleNamespace
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2509_25041_amd as grace
+from workloads import CONFIGS, LayerConfig, make_workload
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    ref = ref.astype(np.float64)
+    got = got.astype(np.float64)
+    if ref.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    den = np.maximum(np.abs(ref), max(rms, 1e-30))
+    return float(np.max(np.abs(got - ref) / den))
+
+
+def dev(a: np.ndarray, dtype: str = None) -> torch.Tensor:
+    """host array -> device tensor; uint16 arrays are bf16 bit patterns."""
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
+
+
+def host(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    grace.load_library()
+
+
+def run_route_permute(wl, pl, k, local_rank, rr_in=None, renorm=1, with_rows=True):
+    table = grace.GraceTable.from_placement(pl)
+    logits = dev(wl.logits)
+    rin = None if rr_in is None else torch.from_numpy(rr_in.view(np.int32)).cuda()
+    rout = torch.empty(pl.E, dtype=torch.int32, device="cuda")
+    te, tw, ti, cnt = grace.grace_route(table, local_rank, logits, k, renorm, rin, rout)
+    x = dev(wl.x) if with_rows else None
+    pos, src, ioff, roff, noff, xp = grace.grace_permute(table, ti, x)
+    torch.cuda.synchronize()
+    return table, SimpleNamespace(te=te, tw=tw, ti=ti, cnt=cnt, rout=rout, pos=pos, src=src, ioff=ioff, roff=roff,
+                                  noff=noff, xp=xp, x=x)
+
+
+def check_route_permute(g, ref, wl, k):
+    np.testing.assert_array_equal(host(g.te), ref.topk_expert)
+    np.testing.assert_array_equal(host(g.ti), ref.topk_inst)
+    np.testing.assert_array_equal(host(g.cnt), ref.expert_count)
+    np.testing.assert_array_equal(host(g.rout).view(np.uint32), ref.rr_out)
+    np.testing.assert_allclose(host(g.tw), ref.topk_weight, rtol=1e-6, atol=0)
+    np.testing.assert_array_equal(host(g.pos), ref.perm.perm_pos)
+    np.testing.assert_array_equal(host(g.src), ref.perm.perm_src)
+    np.testing.assert_array_equal(host(g.ioff), ref.perm.inst_off)
+    np.testing.assert_array_equal(host(g.roff), ref.perm.rank_off)
+    np.testing.assert_array_equal(host(g.noff), ref.perm.node_off)
+    if g.xp is not None:
+        np.testing.assert_array_equal(host(g.xp), oracle.gather_rows(wl.x, ref.perm.perm_src, k))
+
+
+# ------------------------------------------------------- routing + permutation --
+@pytest.mark.parametrize("name,T,local_rank", [
+    ("tiny", None, 0), ("tiny", None, 3), ("tiny", 1, 1), ("tiny", 63, 2), ("tiny", 65, 0), ("tiny", 1000, 1),
+    ("olmoe", None, 0), ("olmoe", 777, 2),
+    ("mixtral", 2048, 0), ("mixtral", 2048, 5),
+    ("qwen", None, 0), ("qwen", 3001, 7),
+    ("dsv2lite", None, 0), ("dsv2lite", 5000, 17),
+])
+def test_route_and_permute_bit_exact(name, T, local_rank):
+    cfg = CONFIGS[name]
+    with_rows = (T or cfg.T) * cfg.k * cfg.d <= 2 ** 27      # full-size rows are covered by the layer tests
+    wl = make_workload(cfg, T=T)
+    ref = oracle.route_permute(wl.logits, wl.placement, cfg.k, local_rank)
+    _, g = run_route_permute(wl, wl.placement, cfg.k, local_rank, with_rows=with_rows)
+    check_route_permute(g, ref, wl, cfg.k)
+
+
+def test_route_rr_carry_and_no_renorm():
+    cfg = CONFIGS["dsv2lite"]
+    wl = make_workload(cfg, T=3000)
+    rr_in = np.random.default_rng(5).integers(0, 2 ** 32, size=cfg.E, dtype=np.uint64).astype(np.uint32)
+    rr_in[:8] = [0, 1, 2, 3, 4, 5, 2 ** 32 - 1, 2 ** 31]
+    ref = oracle.route_permute(wl.logits, wl.placement, cfg.k, 9, renorm=0, rr_in=rr_in)
+    _, g = run_route_permute(wl, wl.placement, cfg.k, 9, rr_in=rr_in, renorm=0, with_rows=False)
+    check_route_permute(g, ref, wl, cfg.k)
+
+
+@pytest.mark.parametrize("E,k,T", [(128, 8, 1500), (200, 5, 700), (256, 64, 300), (8, 8, 100), (3, 1, 129)])
+def test_route_wide_and_degenerate_expert_counts(E, k, T):
+    """More than one expert per lane (E > 64), k = E, k = 1, ties everywhere."""
+    rng = np.random.default_rng(E + k)
+    R, N = 6, 3
+    hosts = [sorted(rng.choice(R, size=rng.integers(1, 4), replace=False).tolist()) for _ in range(E)]
+    inst_ptr = np.concatenate([[0], np.cumsum([len(h) for h in hosts])]).astype(np.int32)
+    pl = SimpleNamespace(E=E, R=R, N=N, rank_node=np.array([0, 0, 1, 1, 2, 2], np.int32),
+                         poll_weight=rng.integers(1, 9, size=R).astype(np.uint32), inst_ptr=inst_ptr,
+                         inst_rank=np.concatenate(hosts).astype(np.int32))
+    logits = np.round(rng.standard_normal((T, E)) * 2).astype(np.float32) / 2      # heavy ties
+    logits[0, :] = 0.0
+    logits[1, ::2] = -0.0
+    wl = SimpleNamespace(logits=logits, x=rng.standard_normal((T, 8)).astype(np.float32))
+    ref = oracle.route_permute(logits, pl, k, 2)
+    _, g = run_route_permute(wl, pl, k, 2)
+    check_route_permute(g, ref, wl, k)
+
+
+def test_empty_call_and_argument_errors():
+    cfg = CONFIGS["tiny"]
+    wl = make_workload(cfg)
+    pl = wl.placement
+    table = grace.GraceTable.from_placement(pl)
+    empty = torch.empty((0, cfg.E), dtype=torch.float32, device="cuda")
+    rout = torch.full((cfg.E,), 7, dtype=torch.int32, device="cuda")
+    rin = torch.arange(cfg.E, dtype=torch.int32, device="cuda")
+    te, tw, ti, cnt = grace.grace_route(table, 0, empty, cfg.k, 1, rin, rout)
+    pos, src, ioff, roff, noff, xp = grace.grace_permute(table, ti, torch.empty((0, cfg.d), device="cuda"))
+    torch.cuda.synchronize()
+    assert host(cnt).tolist() == [0] * cfg.E
+    ref = oracle.route_permute(np.zeros((0, cfg.E), np.float32), pl, cfg.k, 0, rr_in=np.arange(cfg.E, dtype=np.uint32))
+    np.testing.assert_array_equal(host(rout).view(np.uint32), ref.rr_out)
+    assert host(ioff).tolist() == [0] * (pl.I + 1) and host(roff).tolist() == [0] * (pl.R + 1)
+    assert host(noff).tolist() == [0] * (pl.N + 1)
+    logits = dev(wl.logits)
+    for bad in (dict(k=0), dict(k=cfg.E + 1), dict(local_rank=pl.R), dict(local_rank=-1)):
+        a = {**dict(k=cfg.k, local_rank=0), **bad}
+        with pytest.raises(grace.GraceError):
+            grace.grace_route(table, a["local_rank"], logits, a["k"])
+    with pytest.raises(grace.GraceError):      # E of the logits differs from the table's
+        grace.grace_route(table, 0, torch.zeros((4, cfg.E + 1), device="cuda"), 2)
+    with pytest.raises(grace.GraceError):      # 12-byte rows
+        grace.grace_permute(table, torch.zeros((4, cfg.k), dtype=torch.int32, device="cuda"),
+                            torch.zeros((4, 3), device="cuda"))
+    table.destroy()
+    with pytest.raises(ValueError):
+        grace.grace_route(table, 0, logits, cfg.k)
+
+
+# ------------------------------------------------------------------- combine --
+@pytest.mark.parametrize("name,T,shared", [("tiny", None, False), ("tiny", 77, True), ("olmoe", 512, False),
+                                           ("qwen", 300, True)])
+def test_combine_matches_oracle_and_identity_experts(name, T, shared):
+    cfg = CONFIGS[name]
+    wl = make_workload(cfg, T=T)
+    T = wl.logits.shape[0]
+    ref = oracle.route_permute(wl.logits, wl.placement, cfg.k, 0)
+    _, g = run_route_permute(wl, wl.placement, cfg.k, 0)
+    # identity experts: y = xp, sum_j w_j = 1  ->  out = x
+    out = grace.grace_combine(g.xp, g.pos, g.tw)
+    x64 = oracle.widen(wl.x)
+    assert rel_err(oracle.widen(host(out)), x64) <= (1e-6 if cfg.dtype == "f32" else 2.0 ** -8)
+    # arbitrary y, optional shared term, against the oracle on the same stored values
+    rng = np.random.default_rng(1)
+    y = rng.standard_normal((T * cfg.k, cfg.d)).astype(np.float32)
+    ys = rng.standard_normal((T, cfg.d)).astype(np.float32)
+    if cfg.dtype == "bf16":
+        from workloads import f32_to_bf16_bits
+        y, ys = f32_to_bf16_bits(y), f32_to_bf16_bits(ys)
+    out = grace.grace_combine(dev(y), g.pos, g.tw, dev(ys) if shared else None)
+    want = oracle.combine(oracle.widen(y), ref.perm.perm_pos, ref.topk_weight, oracle.widen(ys) if shared else None)
+    tol = 1e-6 if cfg.dtype == "f32" else 2.0 ** -8     # one bf16 rounding of an fp32 sum
+    assert rel_err(oracle.widen(host(out)), want) <= tol
+
+
+# ----------------------------------------------------------------------- FFN --
+def _weights64(wl):
+    cache = {}
+
+    def weights_of(e):
+        if e not in cache:
+            cache[e] = tuple(oracle.widen(w) for w in wl.expert_weights(e))
+        return cache[e]
+    return weights_of
+
+
+def _stack_dev(wl, experts):
+    return tuple(dev(w) for w in wl.stacked_weights(list(experts)))
+
+
+SMALL = {
+    "tiny": CONFIGS["tiny"],
+    "bf16_small": LayerConfig("bf16_small", T=700, E=16, k=4, d=256, f=384, dtype="bf16", zipf_s=1.2, nodes=2,
+                              gpus_per_node=2, n_hot=2, replica_mode="all", n_shared=2, seed=11),
+    "bf16_ragged": LayerConfig("bf16_ragged", T=333, E=8, k=2, d=136, f=200, dtype="bf16", zipf_s=0.8, nodes=2,
+                               gpus_per_node=3, n_hot=2, replica_mode="per_node", n_shared=1, seed=12),
+    "f32_ragged": LayerConfig("f32_ragged", T=150, E=6, k=3, d=100, f=76, dtype="f32", zipf_s=1.0, nodes=1,
+                              gpus_per_node=3, n_hot=1, replica_mode="eq3", n_shared=3, seed=13),
+}
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_whole_layer_every_rank_element_by_element(name):
+    """grace_expert_ffn looped over all virtual ranks rebuilds the whole layer;
+    every intermediate is compared with the oracle element by element."""
+    cfg = SMALL[name]
+    wl = make_workload(cfg)
+    pl = wl.placement
+    tol = TOL[cfg.dtype]
+    ref = oracle.route_permute(wl.logits, pl, cfg.k, 1)
+    table, g = run_route_permute(wl, pl, cfg.k, 1)
+    check_route_permute(g, ref, wl, cfg.k)
+    x64 = oracle.widen(wl.x)
+    w64 = _weights64(wl)
+    y = torch.zeros((cfg.T * cfg.k, cfg.d), dtype=g.xp.dtype, device="cuda")
+    for r in range(pl.R):
+        experts = table.local_experts(r)
+        np.testing.assert_array_equal(experts, ref.order.g_expert[ref.order.rank_ptr[r]:ref.order.rank_ptr[r + 1]])
+        wg, wu, wd = _stack_dev(wl, experts)
+        before = y.clone()
+        grace.grace_expert_ffn(table, r, g.xp, g.ioff, cfg.T, cfg.k, wg, wu, wd, y=y)
+        torch.cuda.synchronize()
+        lo, hi = int(ref.perm.rank_off[r]), int(ref.perm.rank_off[r + 1])
+        mask = np.ones(cfg.T * cfg.k, bool)
+        mask[lo:hi] = False
+        np.testing.assert_array_equal(host(y)[mask], host(before)[mask])      # other ranks' rows untouched
+        want = oracle.expert_ffn(ref, x64, cfg.k, [r], w64)
+        assert rel_err(oracle.widen(host(y))[lo:hi], want[lo:hi]) <= tol, f"rank {r}"
+    y_ref = oracle.expert_ffn(ref, x64, cfg.k, range(pl.R), w64)
+    ys = ys_ref = None
+    sh = wl.shared_weights()
+    if sh is not None:
+        ys = grace.grace_shared_ffn(g.x, *[dev(w) for w in sh])
+        ys_ref = oracle.shared_ffn(x64, tuple(oracle.widen(w) for w in sh))
+        assert rel_err(oracle.widen(host(ys)), ys_ref) <= tol
+    out = grace.grace_combine(y, g.pos, g.tw, ys)
+    out_ref = oracle.combine(y_ref, ref.perm.perm_pos, ref.topk_weight, ys_ref)
+    assert rel_err(oracle.widen(host(out)), out_ref) <= tol
+
+
+def test_layer_object_rank_share_matches_oracle():
+    cfg = SMALL["bf16_small"]
+    wl = make_workload(cfg)
+    pl = wl.placement
+    table = grace.GraceTable.from_placement(pl)
+    lr = 2
+    wg, wu, wd = _stack_dev(wl, table.local_experts(lr))
+    sh = tuple(dev(w) for w in wl.shared_weights())
+    layer = grace.GraceMoELayer(table, lr, cfg.T, cfg.k, cfg.d, cfg.f, torch.bfloat16, wg, wu, wd, shared=sh)
+    logits, x = dev(wl.logits), dev(wl.x)
+    for _ in range(2):       # buffers are reused between calls
+        out = layer.forward(logits, x)
+    torch.cuda.synchronize()
+    ref = oracle.route_permute(wl.logits, pl, cfg.k, lr)
+    x64 = oracle.widen(wl.x)
+    y_ref = oracle.expert_ffn(ref, x64, cfg.k, [lr], _weights64(wl))
+    ys_ref = oracle.shared_ffn(x64, tuple(oracle.widen(w) for w in wl.shared_weights()))
+    out_ref = oracle.combine(y_ref, ref.perm.perm_pos, ref.topk_weight, ys_ref)
+    assert rel_err(oracle.widen(host(out)), out_ref) <= TOL["bf16"]
+
+
+# ------------------------------------------- full-size configs, sampled outputs --
+@pytest.mark.parametrize("name", ["olmoe", "qwen", "dsv2lite", "mixtral"])
+def test_full_size_rank_share_sampled(name):
+    """BASELINE sizes in the launch configuration bench.py times (one
+    GraceMoELayer.forward): integers bit-exact over the whole call, FFN rows and
+    final outputs compared on samples the oracle computes one by one."""
+    cfg = CONFIGS[name]
+    wl = make_workload(cfg)
+    pl = wl.placement
+    lr = cfg.local_rank
+    table = grace.GraceTable.from_placement(pl)
+    experts = table.local_experts(lr)
+    wg, wu, wd = _stack_dev(wl, experts)
+    sh = wl.shared_weights()
+    shd = None if sh is None else tuple(dev(w) for w in sh)
+    layer = grace.GraceMoELayer(table, lr, cfg.T, cfg.k, cfg.d, cfg.f, torch.bfloat16, wg, wu, wd, shared=shd)
+    out = layer.forward(dev(wl.logits), dev(wl.x))
+    torch.cuda.synchronize()
+    ref = oracle.route_permute(wl.logits, pl, cfg.k, lr)
+    te, tw, ti, cnt = layer.route_out
+    pos, src, ioff, roff, noff = layer.perm_out
+    g = SimpleNamespace(te=te, tw=tw, ti=ti, cnt=cnt, rout=None, pos=pos, src=src, ioff=ioff, roff=roff, noff=noff,
+                        xp=None)
+    np.testing.assert_array_equal(host(te), ref.topk_expert)
+    np.testing.assert_array_equal(host(ti), ref.topk_inst)
+    np.testing.assert_array_equal(host(pos), ref.perm.perm_pos)
+    np.testing.assert_array_equal(host(src), ref.perm.perm_src)
+    np.testing.assert_array_equal(host(ioff), ref.perm.inst_off)
+    np.testing.assert_array_equal(host(roff), ref.perm.rank_off)
+    np.testing.assert_array_equal(host(noff), ref.perm.node_off)
+    rng = np.random.default_rng(0)
+    # dispatch buffer rows, bit for bit, on a sample of positions
+    ps = rng.choice(cfg.T * cfg.k, size=512, replace=False)
+    np.testing.assert_array_equal(host(layer.xp[torch.from_numpy(ps).cuda()]), wl.x[ref.perm.perm_src[ps] // cfg.k])
+    # FFN rows of the local share: first/last row of every local instance + random ones
+    lo, hi = int(ref.perm.rank_off[lr]), int(ref.perm.rank_off[lr + 1])
+    x64 = oracle.widen(wl.x)
+    w64 = _weights64(wl)
+    n_sample = 24 if cfg.d * cfg.f > 2 ** 24 else 96
+    rows = set()
+    for gi in range(int(ref.order.rank_ptr[lr]), int(ref.order.rank_ptr[lr + 1])):
+        a, b = int(ref.perm.inst_off[gi]), int(ref.perm.inst_off[gi + 1])
+        if b > a:
+            rows.update([a, b - 1])
+    if hi > lo:
+        rows.update(rng.integers(lo, hi, size=n_sample).tolist())
+    rows = np.array(sorted(rows), dtype=np.int64)
+    y_ref = oracle.expert_ffn(ref, x64, cfg.k, [lr], w64, threads=8, rows=rows)
+    y_got = oracle.widen(host(layer.y[torch.from_numpy(rows).cuda()]))
+    assert rel_err(y_got, y_ref[rows]) <= TOL["bf16"]
+    # final outputs of sampled tokens: needs every local row of those tokens
+    toks = rng.choice(cfg.T, size=16, replace=False)
+    need = ref.perm.perm_pos.reshape(cfg.T, cfg.k)[toks].reshape(-1)
+    need = need[(need >= lo) & (need < hi)]
+    y_tok = oracle.expert_ffn(ref, x64, cfg.k, [lr], w64, threads=8, rows=need)
+    ys_ref = None
+    if sh is not None:
+        ys_ref = oracle.shared_ffn(x64, tuple(oracle.widen(w) for w in sh), threads=8, rows=toks)
+    out_ref = oracle.combine(y_tok, ref.perm.perm_pos, ref.topk_weight, ys_ref)
+    assert rel_err(oracle.widen(host(out[torch.from_numpy(toks).cuda()])), out_ref[toks]) <= TOL["bf16"]
+    # properties that hold at any size: rows outside the local share stay zero
+    if lo > 0:
+        assert not bool(layer.y[:lo].any())
+    if hi < cfg.T * cfg.k:
+        assert not bool(layer.y[hi:].any())
