@@ -175,6 +175,18 @@ int grace_expert_ffn(const grace_table *table, int32_t rank, const void *xp, con
                      int32_t k, int32_t d, int32_t f, grace_dtype dt, const void *w_gate, const void *w_up,
                      const void *w_down, void *y, void *ws, void *stream);
 
+/* The two launches of grace_expert_ffn as separate calls, for callers that
+ * interleave other work between them or time them individually:
+ * _up writes the hidden activation silu(W_gate xp) * (W_up xp) of the rank's
+ * rows to ws ([T*k, f] of dt, row p at the same index as in xp); _down reads it
+ * from ws and writes y.  grace_expert_ffn(...) == _up(...) then _down(...) with
+ * the same ws.  Arguments and limits as for grace_expert_ffn. */
+int grace_expert_ffn_up(const grace_table *table, int32_t rank, const void *xp, const int32_t *inst_off, int32_t T,
+                        int32_t k, int32_t d, int32_t f, grace_dtype dt, const void *w_gate, const void *w_up,
+                        void *ws, void *stream);
+int grace_expert_ffn_down(const grace_table *table, int32_t rank, const int32_t *inst_off, int32_t T, int32_t k,
+                          int32_t d, int32_t f, grace_dtype dt, const void *w_down, void *y, void *ws, void *stream);
+
 /* Always-on shared experts evaluated on all T token rows and summed:
  *     y_shared[t] = sum_s W_down[s] ( silu(W_gate[s] x[t]) * (W_up[s] x[t]) ).
  * DEVICE: x [T,d]; w_gate, w_up [n_shared,f,d]; w_down [n_shared,d,f];

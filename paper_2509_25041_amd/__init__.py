@@ -14,6 +14,8 @@ from .binding import (  # noqa: F401
     GraceTable,
     grace_combine,
     grace_expert_ffn,
+    grace_expert_ffn_down,
+    grace_expert_ffn_up,
     grace_last_error,
     grace_permute,
     grace_route,

@@ -16,7 +16,7 @@ _STATUS = {0: "GRACE_OK", -1: "GRACE_EINVAL", -2: "GRACE_ESHAPE", -3: "GRACE_ETA
 
 EXPORTS = ("grace_table_validate", "grace_table_create", "grace_table_destroy", "grace_table_info",
            "grace_table_instances", "grace_table_local_experts", "grace_workspace_bytes", "grace_route",
-           "grace_permute", "grace_expert_ffn", "grace_shared_ffn", "grace_combine", "grace_last_error")
+           "grace_permute", "grace_expert_ffn", "grace_expert_ffn_up", "grace_expert_ffn_down", "grace_shared_ffn", "grace_combine", "grace_last_error")
 
 _lib: Optional[C.CDLL] = None
 
@@ -53,6 +53,8 @@ def load_library() -> C.CDLL:
     lib.grace_route.argtypes = [vp, i32, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.grace_permute.argtypes = [vp, vp, i32, i32, vp, i32, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.grace_expert_ffn.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp, vp]
+    lib.grace_expert_ffn_up.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp]
+    lib.grace_expert_ffn_down.argtypes = [vp, i32, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp]
     lib.grace_shared_ffn.argtypes = [vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp, vp]
     lib.grace_combine.argtypes = [vp, vp, vp, i32, i32, i32, C.c_int, vp, vp, vp]
     for name in EXPORTS:
@@ -225,6 +227,20 @@ def grace_expert_ffn(table: GraceTable, rank: int, xp: torch.Tensor, inst_off: t
                                            _dp(w_gate) if S else None, _dp(w_up) if S else None,
                                            _dp(w_down) if S else None, _dp(y), _dp(ws), _stream()))
     return y
+
+
+def grace_expert_ffn_up(table: GraceTable, rank: int, xp: torch.Tensor, inst_off: torch.Tensor, T: int, k: int,
+                        w_gate: torch.Tensor, w_up: torch.Tensor, ws: torch.Tensor) -> None:
+    S, f, d = w_gate.shape
+    _check(load_library().grace_expert_ffn_up(table.handle, rank, _dp(xp), _dp(inst_off), T, k, d, f, _dtype_code(xp),
+                                              _dp(w_gate) if S else None, _dp(w_up) if S else None, _dp(ws), _stream()))
+
+
+def grace_expert_ffn_down(table: GraceTable, rank: int, inst_off: torch.Tensor, T: int, k: int, w_down: torch.Tensor,
+                          y: torch.Tensor, ws: torch.Tensor) -> None:
+    S, d, f = w_down.shape
+    _check(load_library().grace_expert_ffn_down(table.handle, rank, _dp(inst_off), T, k, d, f, _dtype_code(y),
+                                                _dp(w_down) if S else None, _dp(y), _dp(ws), _stream()))
 
 
 def grace_shared_ffn(x: torch.Tensor, w_gate: torch.Tensor, w_up: torch.Tensor, w_down: torch.Tensor,

@@ -33,7 +33,7 @@ const char *last_error();
 constexpr int WAVE = 64;
 
 // Assignments are ranked in chunks; one wavefront owns one chunk.
-constexpr int ROUTE_TOKENS_PER_CHUNK = 64;   // route: chunk = 64 tokens = 64*k assignments
+constexpr int ROUTE_TOKENS_PER_CHUNK = 32;   // route: chunk = 32 tokens = 32*k assignments
 constexpr int PERM_CHUNK = 512;              // permute: chunk = 512 assignments
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

@@ -294,40 +294,63 @@ static int check_ffn_shapes(const char *who, int32_t d, int32_t f, grace_dtype d
 
 using namespace grace;
 
-extern "C" int grace_expert_ffn(const grace_table *table, int32_t rank, const void *xp, const int32_t *inst_off,
-                                int32_t T, int32_t k, int32_t d, int32_t f, grace_dtype dt, const void *w_gate,
-                                const void *w_up, const void *w_down, void *y, void *ws, void *stream) {
-    if (!table) return fail(GRACE_EINVAL, "expert_ffn: table is null");
-    if (rank < 0 || rank >= table->R) return fail(GRACE_EINVAL, "expert_ffn: rank=%d outside [0,%d)", rank, table->R);
-    if (T < 0 || k < 1) return fail(GRACE_EINVAL, "expert_ffn: T=%d, k=%d invalid", T, k);
-    if ((int64_t)T * k > INT32_MAX) return fail(GRACE_ESHAPE, "expert_ffn: T*k exceeds 2^31-1");
-    int rc = check_ffn_shapes("expert_ffn", d, f, dt);
+static int expert_ffn_common(const char *who, const grace_table *table, int32_t rank, int32_t T, int32_t k, int32_t d,
+                             int32_t f, grace_dtype dt, int &g0, int &S) {
+    if (!table) return fail(GRACE_EINVAL, "%s: table is null", who);
+    if (rank < 0 || rank >= table->R) return fail(GRACE_EINVAL, "%s: rank=%d outside [0,%d)", who, rank, table->R);
+    if (T < 0 || k < 1) return fail(GRACE_EINVAL, "%s: T=%d, k=%d invalid", who, T, k);
+    if ((int64_t)T * k > INT32_MAX) return fail(GRACE_ESHAPE, "%s: T*k exceeds 2^31-1", who);
+    int rc = check_ffn_shapes(who, d, f, dt);
     if (rc != GRACE_OK) return rc;
-    const int g0 = table->rank_ptr[rank];
-    const int S = table->rank_ptr[rank + 1] - g0;
+    g0 = table->rank_ptr[rank];
+    S = table->rank_ptr[rank + 1] - g0;
+    return GRACE_OK;
+}
+
+extern "C" int grace_expert_ffn_up(const grace_table *table, int32_t rank, const void *xp, const int32_t *inst_off,
+                                   int32_t T, int32_t k, int32_t d, int32_t f, grace_dtype dt, const void *w_gate,
+                                   const void *w_up, void *ws, void *stream) {
+    int g0, S;
+    int rc = expert_ffn_common("expert_ffn_up", table, rank, T, k, d, f, dt, g0, S);
+    if (rc != GRACE_OK) return rc;
     if (S == 0 || T == 0) return GRACE_OK;
-    if (!xp || !inst_off || !w_gate || !w_up || !w_down || !y || !ws)
-        return fail(GRACE_EINVAL, "expert_ffn: null device pointer");
-    if ((((uintptr_t)xp) | ((uintptr_t)w_gate) | ((uintptr_t)w_up) | ((uintptr_t)w_down) | ((uintptr_t)y) |
-         ((uintptr_t)ws)) & 15)
-        return fail(GRACE_EINVAL, "expert_ffn: device pointers must be 16-byte aligned");
-    hipStream_t st = (hipStream_t)stream;
-    const int64_t n_rows = (int64_t)T * k;
+    if (!xp || !inst_off || !w_gate || !w_up || !ws) return fail(GRACE_EINVAL, "expert_ffn_up: null device pointer");
+    if ((((uintptr_t)xp) | ((uintptr_t)w_gate) | ((uintptr_t)w_up) | ((uintptr_t)ws)) & 15)
+        return fail(GRACE_EINVAL, "expert_ffn_up: device pointers must be 16-byte aligned");
     GemmArgs up{};
     up.A = xp; up.lda = d;
     up.B0 = w_gate; up.B1 = w_up; up.b_slot_stride = (int64_t)d * f; up.ldb = d;
     up.N = f; up.K = d; up.kseg_len = d; up.kseg_stride = 0;
     up.out = ws; up.ldo = f;
     up.seg_off = inst_off + g0; up.S = S; up.M_single = 0;
-    rc = launch_gemm<true>(up, dt, n_rows, st, "expert_ffn up projection");
+    return launch_gemm<true>(up, dt, (int64_t)T * k, (hipStream_t)stream, "expert_ffn up projection");
+}
+
+extern "C" int grace_expert_ffn_down(const grace_table *table, int32_t rank, const int32_t *inst_off, int32_t T,
+                                     int32_t k, int32_t d, int32_t f, grace_dtype dt, const void *w_down, void *y,
+                                     void *ws, void *stream) {
+    int g0, S;
+    int rc = expert_ffn_common("expert_ffn_down", table, rank, T, k, d, f, dt, g0, S);
     if (rc != GRACE_OK) return rc;
+    if (S == 0 || T == 0) return GRACE_OK;
+    if (!inst_off || !w_down || !y || !ws) return fail(GRACE_EINVAL, "expert_ffn_down: null device pointer");
+    if ((((uintptr_t)w_down) | ((uintptr_t)y) | ((uintptr_t)ws)) & 15)
+        return fail(GRACE_EINVAL, "expert_ffn_down: device pointers must be 16-byte aligned");
     GemmArgs dn{};
     dn.A = ws; dn.lda = f;
     dn.B0 = w_down; dn.B1 = nullptr; dn.b_slot_stride = (int64_t)d * f; dn.ldb = f;
     dn.N = d; dn.K = f; dn.kseg_len = f; dn.kseg_stride = 0;
     dn.out = y; dn.ldo = d;
     dn.seg_off = inst_off + g0; dn.S = S; dn.M_single = 0;
-    return launch_gemm<false>(dn, dt, n_rows, st, "expert_ffn down projection");
+    return launch_gemm<false>(dn, dt, (int64_t)T * k, (hipStream_t)stream, "expert_ffn down projection");
+}
+
+extern "C" int grace_expert_ffn(const grace_table *table, int32_t rank, const void *xp, const int32_t *inst_off,
+                                int32_t T, int32_t k, int32_t d, int32_t f, grace_dtype dt, const void *w_gate,
+                                const void *w_up, const void *w_down, void *y, void *ws, void *stream) {
+    int rc = grace_expert_ffn_up(table, rank, xp, inst_off, T, k, d, f, dt, w_gate, w_up, ws, stream);
+    if (rc != GRACE_OK) return rc;
+    return grace_expert_ffn_down(table, rank, inst_off, T, k, d, f, dt, w_down, y, ws, stream);
 }
 
 extern "C" int grace_shared_ffn(const void *x, int32_t T, int32_t d, int32_t f, int32_t n_shared, grace_dtype dt,

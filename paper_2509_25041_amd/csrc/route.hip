@@ -1,9 +1,10 @@
 // grace_route: top-k gating, per-expert request counter, locality-first replica pick.
 //
 // Three launches, all integer-exact and free of order-dependent atomics:
-//   1. topk_kernel   one wavefront per token: k rounds of wave-wide arg-max over
-//                    (logit desc, expert id asc), softmax weights, and a histogram
-//                    of the chosen experts per chunk of 64 tokens;
+//   1. topk_kernel   one wavefront per token: every lane ranks its logits against
+//                    all others by (logit desc, expert id asc) through scalar
+//                    broadcasts, ranks < k are the choices; softmax weights and a
+//                    histogram of the chosen experts per chunk of tokens;
 //   2. route_scan    exclusive scan of the chunk histograms per expert -> the
 //                    number of earlier requests of each expert before each chunk
 //                    (the weighted round-robin counter of Section 4.3);
@@ -24,23 +25,32 @@ __device__ __forceinline__ float from_ordered_bits(uint32_t o) {
     return __uint_as_float((o & 0x80000000u) ? (o ^ 0x80000000u) : ~o);
 }
 
+constexpr int TOPK_THREADS = 512;                                   // 8 wavefronts per chunk
+constexpr int TOPK_TOK_PER_WAVE = ROUTE_TOKENS_PER_CHUNK / (TOPK_THREADS / 64);
+
+// One wavefront per token, VPL experts per lane.  Instead of k rounds of
+// arg-max, every lane learns the rank of its own logits: each lane's key is
+// broadcast through a scalar register (v_readlane) and compared against the
+// local keys, so after E broadcasts rank = number of larger keys.  Keys are
+// distinct (they include the expert id), so ranks are a permutation and the
+// expert with rank j < k is the token's j-th choice.
 template <int VPL>
-__global__ __launch_bounds__(256) void topk_kernel(const float *__restrict__ logits, int T, int E, int k, int renorm,
-                                                   int32_t *__restrict__ topk_expert,
-                                                   float *__restrict__ topk_weight,
-                                                   int32_t *__restrict__ chunk_hist) {
+__global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *__restrict__ logits, int T, int E, int k,
+                                                            int renorm, int32_t *__restrict__ topk_expert,
+                                                            float *__restrict__ topk_weight,
+                                                            int32_t *__restrict__ chunk_hist) {
     __shared__ int32_t hist[GRACE_MAX_EXPERTS];
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int i = tid; i < E; i += 256) hist[i] = 0;
+    for (int i = tid; i < E; i += TOPK_THREADS) hist[i] = 0;
     __syncthreads();
     const int chunk = (int)blockIdx.x;
-    constexpr int TOK_PER_WAVE = ROUTE_TOKENS_PER_CHUNK / 4;
-    const int t_begin = chunk * ROUTE_TOKENS_PER_CHUNK + wave * TOK_PER_WAVE;
-    for (int i = 0; i < TOK_PER_WAVE; ++i) {
+    const int t_begin = chunk * ROUTE_TOKENS_PER_CHUNK + wave * TOPK_TOK_PER_WAVE;
+    for (int i = 0; i < TOPK_TOK_PER_WAVE; ++i) {
         const int t = t_begin + i;
         if (t >= T) break;  // uniform per wavefront
         float val[VPL];
         uint64_t key[VPL];
+        int rank[VPL];
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
             const int e = lane + 64 * v;
@@ -48,43 +58,47 @@ __global__ __launch_bounds__(256) void topk_kernel(const float *__restrict__ log
             if (x == 0.0f) x = 0.0f;  // -0.0 and +0.0 compare equal: make them the same bits
             val[v] = x;
             // larger key wins: value first, then the lower expert id
-            key[v] = ((uint64_t)ordered_bits(x) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)e);
-            if (e >= E) key[v] = 0;
+            key[v] = (e < E) ? (((uint64_t)ordered_bits(x) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)e)) : 0ull;
+            rank[v] = 0;
         }
-        int my_e = 0;
-        float my_l = 0.0f;
-        for (int j = 0; j < k; ++j) {
-            uint64_t best = 0;
+        float mx = -INFINITY;
 #pragma unroll
-            for (int v = 0; v < VPL; ++v) best = key[v] > best ? key[v] : best;
-            best = wave_max_u64(best);
-            const int e = (int)(0xFFFFFFFFu - (uint32_t)best);
-            if (lane == j) {
-                my_e = e;
-                my_l = from_ordered_bits((uint32_t)(best >> 32));
+        for (int u = 0; u < VPL; ++u) {
+            const int n_src = min(64, E - 64 * u);  // uniform
+            for (int src = 0; src < n_src; ++src) {
+                const uint32_t ohi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(key[u] >> 32), src);
+                const uint32_t olo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)key[u], src);
+                const uint64_t other = ((uint64_t)ohi << 32) | olo;
+#pragma unroll
+                for (int v = 0; v < VPL; ++v) rank[v] += (other > key[v]) ? 1 : 0;
+                mx = fmaxf(mx, from_ordered_bits(ohi));
             }
-#pragma unroll
-            for (int v = 0; v < VPL; ++v)
-                if (lane + 64 * v == e) key[v] = 0;  // taken
         }
-        const float mx = __shfl(my_l, 0, 64);  // the first pick is the maximum logit
-        float part = 0.0f;
+        float ex[VPL], den = 0.0f, sel = 0.0f;
 #pragma unroll
-        for (int v = 0; v < VPL; ++v) part += (lane + 64 * v < E) ? expf(val[v] - mx) : 0.0f;
-        const float den = wave_sum(part);
-        float w = (lane < k) ? expf(my_l - mx) / den : 0.0f;
-        if (renorm) {
-            const float s = wave_sum(w);
-            w = w / s;
+        for (int v = 0; v < VPL; ++v) {
+            ex[v] = (lane + 64 * v < E) ? expf(val[v] - mx) : 0.0f;
+            den += ex[v];
+            sel += (rank[v] < k) ? ex[v] : 0.0f;
         }
-        if (lane < k) {
-            topk_expert[(size_t)t * k + lane] = my_e;
-            topk_weight[(size_t)t * k + lane] = w;
-            atomicAdd(&hist[my_e], 1);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            den += __shfl_xor(den, o, 64);
+            sel += __shfl_xor(sel, o, 64);
+        }
+        const float norm = renorm ? sel : den;
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) {
+            const int e = lane + 64 * v;
+            if (e < E && rank[v] < k) {
+                topk_expert[(size_t)t * k + rank[v]] = e;
+                topk_weight[(size_t)t * k + rank[v]] = ex[v] / norm;
+                atomicAdd(&hist[e], 1);
+            }
         }
     }
     __syncthreads();
-    for (int i = tid; i < E; i += 256) chunk_hist[(size_t)chunk * E + i] = hist[i];
+    for (int i = tid; i < E; i += TOPK_THREADS) chunk_hist[(size_t)chunk * E + i] = hist[i];
 }
 
 __global__ __launch_bounds__(SCAN_THREADS) void route_scan_kernel(const int32_t *__restrict__ hist,
@@ -175,10 +189,10 @@ extern "C" int grace_route(const grace_table *table, int32_t local_rank, const f
     if (nchunks > 0) {
         const int vpl = (E + 63) / 64;
         switch (vpl) {
-            case 1: topk_kernel<1><<<nchunks, 256, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, hist); break;
-            case 2: topk_kernel<2><<<nchunks, 256, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, hist); break;
-            case 3: topk_kernel<3><<<nchunks, 256, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, hist); break;
-            default: topk_kernel<4><<<nchunks, 256, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, hist); break;
+            case 1: topk_kernel<1><<<nchunks, TOPK_THREADS, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, hist); break;
+            case 2: topk_kernel<2><<<nchunks, TOPK_THREADS, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, hist); break;
+            case 3: topk_kernel<3><<<nchunks, TOPK_THREADS, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, hist); break;
+            default: topk_kernel<4><<<nchunks, TOPK_THREADS, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, hist); break;
         }
         GRACE_LAUNCH_CHECK("topk_kernel");
     }

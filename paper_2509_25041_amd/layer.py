@@ -2,12 +2,14 @@
 preallocated buffers (no allocation, no host synchronisation per step)."""
 from __future__ import annotations
 
-from typing import Optional
+from typing import Dict, List, Optional, Tuple
 
 import torch
 
-from .binding import (GraceTable, grace_combine, grace_expert_ffn, grace_permute, grace_route, grace_shared_ffn,
-                      grace_workspace_bytes, _dtype_code)
+from .binding import (GraceTable, _dtype_code, grace_combine, grace_expert_ffn_down, grace_expert_ffn_up,
+                      grace_permute, grace_route, grace_shared_ffn, grace_workspace_bytes)
+
+STAGES = ("route", "permute", "ffn_up", "ffn_down", "shared_ffn", "combine")
 
 
 class GraceMoELayer:
@@ -42,11 +44,28 @@ class GraceMoELayer:
                               device=device)
 
     def forward(self, logits: torch.Tensor, x: torch.Tensor, rr_in: Optional[torch.Tensor] = None,
-                rr_out: Optional[torch.Tensor] = None) -> torch.Tensor:
-        te, tw, ti, cnt = grace_route(self.table, self.local_rank, logits, self.k, self.renorm, rr_in, rr_out,
-                                      ws=self.ws, out=self.route_out)
-        pos, src, ioff, roff, noff, xp = grace_permute(self.table, ti, x, ws=self.ws, out=self.perm_out, xp=self.xp)
-        grace_expert_ffn(self.table, self.local_rank, xp, ioff, self.T, self.k, *self.w, y=self.y, ws=self.ws)
+                rr_out: Optional[torch.Tensor] = None,
+                events: Optional[List[Tuple[str, torch.cuda.Event, torch.cuda.Event]]] = None) -> torch.Tensor:
+        """One layer step.  With `events` (a list to append to), a pair of HIP
+        events is recorded around every library call on the current stream."""
+        def timed(name, fn):
+            if events is None:
+                return fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            r = fn()
+            b.record()
+            events.append((name, a, b))
+            return r
+
+        te, tw, ti, cnt = timed("route", lambda: grace_route(self.table, self.local_rank, logits, self.k, self.renorm,
+                                                             rr_in, rr_out, ws=self.ws, out=self.route_out))
+        pos, src, ioff, roff, noff, xp = timed("permute", lambda: grace_permute(self.table, ti, x, ws=self.ws,
+                                                                                out=self.perm_out, xp=self.xp))
+        timed("ffn_up", lambda: grace_expert_ffn_up(self.table, self.local_rank, xp, ioff, self.T, self.k, self.w[0],
+                                                    self.w[1], self.ws))
+        timed("ffn_down", lambda: grace_expert_ffn_down(self.table, self.local_rank, ioff, self.T, self.k, self.w[2],
+                                                        self.y, self.ws))
         if self.shared is not None:
-            grace_shared_ffn(x, *self.shared, y_shared=self.y_shared, ws=self.ws)
-        return grace_combine(self.y, pos, tw, self.y_shared, out=self.out)
+            timed("shared_ffn", lambda: grace_shared_ffn(x, *self.shared, y_shared=self.y_shared, ws=self.ws))
+        return timed("combine", lambda: grace_combine(self.y, pos, tw, self.y_shared, out=self.out))
