@@ -177,7 +177,7 @@ def main() -> int:
                                f"ranks, local rank {lr}, Zipf s={cfg.zipf_s}", "local_rows": m_loc,
                    "local_slots": int(len(experts)), "rows_per_slot_min_max": [int(seg.min()), int(seg.max())] if len(seg) else [0, 0],
                    "n_shared": cfg.n_shared},
-        "roofline": {"kernel": "gemm_bf16_kernel<true> (grouped gate+up projection with fused SwiGLU)" if cfg.dtype == "bf16"
+        "roofline": {"kernel": "gemm_bf16_fast_kernel<true> (grouped gate+up projection with fused SwiGLU)" if cfg.dtype == "bf16"
                      else "gemm_f32_kernel<true>",
                      "bound": "mfma", "achieved": up_tflops, "peak": PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else 157.3,
                      "unit": "TFLOP/s", "frac": up_tflops / (PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else 157.3),
