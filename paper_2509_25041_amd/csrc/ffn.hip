@@ -21,18 +21,18 @@ namespace grace {
 template <bool FUSED_UP>
 static int launch_gemm(const GemmArgs &g, grace_dtype dt, int64_t m_bound, hipStream_t st, const char *what) {
     if (m_bound <= 0 || g.N <= 0 || g.K <= 0) return GRACE_OK;
-    if (dt == GRACE_BF16 && g.K % fast::BK == 0 && g.kseg_len % fast::BK == 0) {
+    if (dt == GRACE_BF16 && g.K % fast::DefaultGeo::BK == 0 && g.kseg_len % fast::DefaultGeo::BK == 0) {
         // large-tile kernel: needs 128 KB of dynamic LDS, opted into once per process
-        static const hipError_t attr = hipFuncSetAttribute((const void *)fast::gemm_bf16_fast_kernel<FUSED_UP>,
+        static const hipError_t attr = hipFuncSetAttribute((const void *)fast::gemm_bf16_fast_kernel<FUSED_UP, fast::DefaultGeo>,
                                                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                           fast::LDS_BYTES);
+                                                           fast::DefaultGeo::LDS_BYTES);
         if (attr != hipSuccess) return fail(GRACE_EHIP, "%s: cannot reserve LDS: %s", what, hipGetErrorString(attr));
         constexpr int BN = FUSED_UP ? 128 : 256;
         const int64_t mt = m_bound / fast::BM + (g.seg_off ? g.S : 1);
         const int ntn = (g.N + BN - 1) / BN;
         const int64_t grid = fast::grid_blocks(mt, ntn);
         if (grid > INT32_MAX) return fail(GRACE_ESHAPE, "%s: grid too large", what);
-        fast::gemm_bf16_fast_kernel<FUSED_UP><<<(unsigned)grid, fast::THREADS, fast::LDS_BYTES, st>>>(g, ntn);
+        fast::gemm_bf16_fast_kernel<FUSED_UP, fast::DefaultGeo><<<(unsigned)grid, fast::THREADS, fast::DefaultGeo::LDS_BYTES, st>>>(g, ntn);
     } else if (dt == GRACE_BF16) {
         constexpr int BN = FUSED_UP ? 64 : 128;
         const int64_t mt = m_bound / BM + (g.seg_off ? g.S : 1);
