@@ -89,6 +89,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="olmoe", help="olmoe (BASELINE configs[1], default) | qwen | dsv2lite | mixtral | tiny")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device copy kernel (known traffic, for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -120,6 +123,13 @@ def main() -> int:
     tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
     layer = grace.GraceMoELayer(table, lr, cfg.T, cfg.k, cfg.d, cfg.f, tdt, wg, wu, wd, shared=shd)
     logits, x = dev(wl.logits), dev(wl.x)
+
+    if args.calibrate_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         layer.forward(logits, x)
