@@ -28,9 +28,8 @@ static int launch_gemm(const GemmArgs &g, grace_dtype dt, int64_t m_bound, hipSt
                                                            fast::DefaultGeo::LDS_BYTES);
         if (attr != hipSuccess) return fail(GRACE_EHIP, "%s: cannot reserve LDS: %s", what, hipGetErrorString(attr));
         constexpr int BN = FUSED_UP ? 128 : 256;
-        const int64_t mt = m_bound / fast::BM + (g.seg_off ? g.S : 1);
         const int ntn = (g.N + BN - 1) / BN;
-        const int64_t grid = fast::grid_blocks(mt, ntn);
+        const int64_t grid = fast::grid_blocks(m_bound, g.seg_off ? g.S : 1, ntn);
         if (grid > INT32_MAX) return fail(GRACE_ESHAPE, "%s: grid too large", what);
         fast::gemm_bf16_fast_kernel<FUSED_UP, fast::DefaultGeo><<<(unsigned)grid, fast::THREADS, fast::DefaultGeo::LDS_BYTES, st>>>(g, ntn);
     } else if (dt == GRACE_BF16) {

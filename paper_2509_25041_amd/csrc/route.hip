@@ -61,18 +61,25 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *__restr
             key[v] = (e < E) ? (((uint64_t)ordered_bits(x) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)e)) : 0ull;
             rank[v] = 0;
         }
-        float mx = -INFINITY;
+        // Lanes without an expert hold key 0, which beats nothing, so all 64 lanes of every
+        // register are broadcast unconditionally and the loop unrolls with constant lane ids.
 #pragma unroll
         for (int u = 0; u < VPL; ++u) {
-            const int n_src = min(64, E - 64 * u);  // uniform
-            for (int src = 0; src < n_src; ++src) {
+#pragma unroll
+            for (int src = 0; src < 64; ++src) {
                 const uint32_t ohi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(key[u] >> 32), src);
                 const uint32_t olo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)key[u], src);
                 const uint64_t other = ((uint64_t)ohi << 32) | olo;
 #pragma unroll
                 for (int v = 0; v < VPL; ++v) rank[v] += (other > key[v]) ? 1 : 0;
-                mx = fmaxf(mx, from_ordered_bits(ohi));
             }
+        }
+        // the maximum logit belongs to the expert of rank 0
+        float mx = 0.0f;
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) {
+            const uint64_t first = __ballot(rank[v] == 0 && lane + 64 * v < E);
+            if (first) mx = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, val[v]), (int)__builtin_ctzll(first)));
         }
         float ex[VPL], den = 0.0f, sel = 0.0f;
 #pragma unroll
