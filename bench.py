@@ -143,10 +143,11 @@ def main() -> int:
     # timed region: exactly `steps` steps, HIP events around every library call
     # on the stream the kernels run on
     events = []
+    pool = [torch.cuda.Event(enable_timing=True) for _ in range(12 * args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        layer.forward(logits, x, events=events)
+        layer.forward(logits, x, events=events, event_pool=pool)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
@@ -154,6 +155,17 @@ def main() -> int:
     for name, a, b in events:
         per_stage.setdefault(name, []).append(a.elapsed_time(b))
     stage_ms = {k: float(np.mean(v)) for k, v in per_stage.items()}
+
+    # the same step as one HIP graph launch (extra information; `value` stays the eager loop)
+    graph = layer.capture(logits, x)
+    for _ in range(3):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
     d, f, k, T = cfg.d, cfg.f, cfg.k, cfg.T
     el = 4 if cfg.dtype == "f32" else 2
@@ -193,6 +205,7 @@ def main() -> int:
                      "unit": "TFLOP/s", "frac": up_tflops / (PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else 157.3),
                      "traffic": traffic, "avg_launch_ms": stage_ms["ffn_up"]},
         "stages_ms": stage_ms,
+        "graph_replay_ms_per_step": graph_ms,
         "stages_achieved": {
             "ffn_down_TFLOPs": flops_down / (stage_ms["ffn_down"] * 1e-3) / 1e12,
             "route_GBs": bytes_route / (stage_ms["route"] * 1e-3) / 1e9,

@@ -22,6 +22,8 @@
 // round-robin over the XCDs instead balances them better on paper but
 // measured 15-20 % slower on the Zipf-skewed workload.
 #pragma once
+#include <type_traits>
+
 #include "bf16.h"
 #include "gemm_common.h"
 
@@ -205,19 +207,24 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_fast_kernel(const GemmAr
             for (int i = 0; i < 4; ++i) fa[buf][i] = *(const bf16x8_t *)(st + a_off[i] + pc[ks]);
         };
         fetch(0, smem, 0);
-        for (int kt = 0; kt < nk; ++kt) {
+        // One K step.  HAS_NEXT: another step follows (synchronise, fetch its first fragments).
+        // HAS_LOADS: the stage freed at the barrier is refilled; its loads sit in the same basic
+        // block as the last group's MFMAs so that they can be issued one per MFMA.
+        auto step = [&](auto has_loads, auto has_next, int kt) {
+            constexpr bool HAS_LOADS = decltype(has_loads)::value, HAS_NEXT = decltype(has_next)::value;
             const char *st = smem + stage_c * G::STAGE_BYTES;
             stage_c = (stage_c + 1 == NSTAGE) ? 0 : stage_c + 1;
             const char *st_next = smem + stage_c * G::STAGE_BYTES;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 const int cur = ks & 1, nxt = cur ^ 1;  // KS is even: parity restarts every step
-                if (ks == KS - 1) {
-                    if (kt + 1 < nk) {
+                const bool last = ks == KS - 1;
+                if (last) {
+                    if (HAS_NEXT) {
                         wait_younger(min(NSTAGE - 2, nk - 2 - kt));  // in flight: stages kt+2 .. kt+NSTAGE-1
                         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                         asm volatile("s_barrier" ::: "memory");
-                        if (DEBUG != 1 && kt + NSTAGE < nk) issue_loads();
+                        if (HAS_LOADS && DEBUG != 1) issue_loads();
                         if (DEBUG != 2) fetch(nxt, st_next, 0);
                     }
                 } else {
@@ -229,18 +236,33 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_fast_kernel(const GemmAr
 #pragma unroll
                         for (int jj = 0; jj < 2; ++jj)
                             acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][jj], fa[cur][i], acc[i][jj], 0, 0, 0);
-                    // issue order inside this group: the 6 fragment reads of the next
-                    // group are spread between the 8 MFMAs of this one
+                    // issue order inside a group: the 6 fragment reads of the next group (and, after the
+                    // barrier, the 2 * LOADS direct-to-LDS loads) are spread between the 8 MFMAs
+                    if (last && HAS_NEXT && HAS_LOADS && DEBUG != 1) {
 #pragma unroll
-                    for (int r = 0; r < 6; ++r) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
-                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 LDS read
+                        for (int r = 0; r < 8; ++r) {
+                            if (r < 2 * LOADS) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // 1 VMEM
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                      // 1 MFMA
+                            if (r < 6) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);           // 1 LDS read
+                        }
+                    } else if (!last || HAS_NEXT) {
+#pragma unroll
+                        for (int r = 0; r < 6; ++r) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
+                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 LDS read
+                        }
+                        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
                     }
-                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-        }
+        };
+        using T_ = std::integral_constant<bool, true>;
+        using F_ = std::integral_constant<bool, false>;
+        int kt = 0;
+        for (; kt + NSTAGE < nk; ++kt) step(T_{}, T_{}, kt);
+        for (; kt + 1 < nk; ++kt) step(F_{}, T_{}, kt);
+        step(F_{}, F_{}, kt);
     } else {
         for (int kt = 0; kt < nk; ++kt) {
             const char *st = smem + stage_c * G::STAGE_BYTES;

@@ -45,6 +45,16 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *__restr
     __syncthreads();
     const int chunk = (int)blockIdx.x;
     const int t_begin = chunk * ROUTE_TOKENS_PER_CHUNK + wave * TOPK_TOK_PER_WAVE;
+    // all of this wavefront's logits are requested before any is used
+    float raw[TOPK_TOK_PER_WAVE][VPL];
+#pragma unroll
+    for (int i = 0; i < TOPK_TOK_PER_WAVE; ++i)
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) {
+            const int t = t_begin + i, e = lane + 64 * v;
+            raw[i][v] = (t < T && e < E) ? logits[(size_t)t * E + e] : -INFINITY;
+        }
+#pragma unroll
     for (int i = 0; i < TOPK_TOK_PER_WAVE; ++i) {
         const int t = t_begin + i;
         if (t >= T) break;  // uniform per wavefront
@@ -54,7 +64,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *__restr
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
             const int e = lane + 64 * v;
-            float x = (e < E) ? logits[(size_t)t * E + e] : -INFINITY;
+            float x = raw[i][v];
             if (x == 0.0f) x = 0.0f;  // -0.0 and +0.0 compare equal: make them the same bits
             val[v] = x;
             // larger key wins: value first, then the lower expert id

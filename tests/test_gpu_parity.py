@@ -263,6 +263,33 @@ def test_layer_object_rank_share_matches_oracle():
     assert rel_err(oracle.widen(host(out)), out_ref) <= TOL["bf16"]
 
 
+def test_graph_replays_match_eager():
+    """A captured step replayed several times, with eager work and synchronisations in
+    between and inputs changed in place, gives the eager result every time."""
+    cfg = SMALL["bf16_small"]
+    wl = make_workload(cfg)
+    table = grace.GraceTable.from_placement(wl.placement)
+    lr = 1
+    wg, wu, wd = _stack_dev(wl, table.local_experts(lr))
+    sh = tuple(dev(w) for w in wl.shared_weights())
+    layer = grace.GraceMoELayer(table, lr, cfg.T, cfg.k, cfg.d, cfg.f, torch.bfloat16, wg, wu, wd, shared=sh)
+    eager = grace.GraceMoELayer(table, lr, cfg.T, cfg.k, cfg.d, cfg.f, torch.bfloat16, wg, wu, wd, shared=sh)
+    logits, x = dev(wl.logits), dev(wl.x)
+    graph = layer.capture(logits, x)
+    rng = np.random.default_rng(3)
+    for rep in range(4):
+        if rep:
+            logits.copy_(torch.from_numpy(rng.standard_normal(wl.logits.shape).astype(np.float32)).cuda())
+            x.copy_(torch.from_numpy(rng.standard_normal(wl.x.shape).astype(np.float32)).cuda().to(torch.bfloat16))
+        graph.replay()
+        torch.cuda.synchronize()
+        want = eager.forward(logits.clone(), x.clone())
+        torch.cuda.synchronize()
+        assert torch.equal(layer.out, want), f"replay {rep}"
+        for a, b in zip(layer.route_out + layer.perm_out, eager.route_out + eager.perm_out):
+            assert torch.equal(a, b)
+
+
 # ------------------------------------------- full-size configs, sampled outputs --
 @pytest.mark.parametrize("name", ["olmoe", "qwen", "dsv2lite", "mixtral"])
 def test_full_size_rank_share_sampled(name):
