@@ -216,6 +216,13 @@ def main() -> int:
     }
     if sh is not None:
         result["stages_achieved"]["shared_ffn_TFLOPs"] = 6.0 * d * f * cfg.n_shared * T / (stage_ms["shared_ffn"] * 1e-3) / 1e12
+    if cfg.dtype == "bf16":
+        # what the MFMA units sustain on this device (no global traffic), for context next to the nominal peak
+        result["mfma_sustained_TFLOPs"] = {
+            "constant_operands_registers": grace.grace_mfma_sustained(False, False),
+            "random_operands_registers": grace.grace_mfma_sustained(True, False),
+            "random_operands_lds_fed": grace.grace_mfma_sustained(True, True),
+        }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, cfg)
     print(json.dumps(result))

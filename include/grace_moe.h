@@ -205,6 +205,15 @@ int grace_shared_ffn(const void *x, int32_t T, int32_t d, int32_t f, int32_t n_s
 int grace_combine(const void *y, const int32_t *perm_pos, const float *topk_weight, int32_t T, int32_t k, int32_t d,
                   grace_dtype dt, const void *y_shared, void *out, void *stream);
 
+/* ---- diagnostics ---------------------------------------------------------------
+ * Measures the bf16 MFMA rate the current device sustains with the grouped GEMM's
+ * inner instruction mix and no global traffic (8 wavefronts per CU, one barrier
+ * per 32 MFMAs): constant or pseudo-random operands (a power-limited part runs
+ * slower the more operand bits toggle), fragments held in registers or re-read
+ * from LDS.  Allocates a small device buffer, runs for a few tens of
+ * milliseconds on `stream` and synchronises it.  HOST output: TFLOP/s. */
+int grace_mfma_sustained(int32_t random_operands, int32_t lds_fed, double *tflops_out, void *stream);
+
 /* Text of the calling thread's most recent error ("" if none).  The pointer
  * stays valid until the thread's next failing call. */
 const char *grace_last_error(void);

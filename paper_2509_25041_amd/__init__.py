@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     grace_expert_ffn_down,
     grace_expert_ffn_up,
     grace_last_error,
+    grace_mfma_sustained,
     grace_permute,
     grace_route,
     grace_shared_ffn,

@@ -16,7 +16,7 @@ _STATUS = {0: "GRACE_OK", -1: "GRACE_EINVAL", -2: "GRACE_ESHAPE", -3: "GRACE_ETA
 
 EXPORTS = ("grace_table_validate", "grace_table_create", "grace_table_destroy", "grace_table_info",
            "grace_table_instances", "grace_table_local_experts", "grace_workspace_bytes", "grace_route",
-           "grace_permute", "grace_expert_ffn", "grace_expert_ffn_up", "grace_expert_ffn_down", "grace_shared_ffn", "grace_combine", "grace_last_error")
+           "grace_permute", "grace_expert_ffn", "grace_expert_ffn_up", "grace_expert_ffn_down", "grace_shared_ffn", "grace_combine", "grace_mfma_sustained", "grace_last_error")
 
 _lib: Optional[C.CDLL] = None
 
@@ -57,6 +57,7 @@ def load_library() -> C.CDLL:
     lib.grace_expert_ffn_down.argtypes = [vp, i32, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp]
     lib.grace_shared_ffn.argtypes = [vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp, vp]
     lib.grace_combine.argtypes = [vp, vp, vp, i32, i32, i32, C.c_int, vp, vp, vp]
+    lib.grace_mfma_sustained.argtypes = [i32, i32, C.POINTER(C.c_double), vp]
     for name in EXPORTS:
         if name not in ("grace_last_error", "grace_workspace_bytes"):
             getattr(lib, name).restype = C.c_int
@@ -267,3 +268,10 @@ def grace_combine(y: torch.Tensor, perm_pos: torch.Tensor, topk_weight: torch.Te
     _check(load_library().grace_combine(_dp(y), _dp(perm_pos), _dp(topk_weight), T, k, d, _dtype_code(y), _dp(y_shared),
                                         _dp(out), _stream()))
     return out
+
+
+def grace_mfma_sustained(random_operands: bool = True, lds_fed: bool = True) -> float:
+    """Sustained bf16 MFMA TFLOP/s of the current device (see grace_moe.h)."""
+    out = C.c_double()
+    _check(load_library().grace_mfma_sustained(int(random_operands), int(lds_fed), C.byref(out), _stream()))
+    return float(out.value)

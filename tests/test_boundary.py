@@ -74,6 +74,7 @@ def test_null_and_range_checks_without_device():
     assert lib.grace_combine(None, None, None, 1, 1, 3, 1, None, None, None) == -2               # 6-byte rows
     assert lib.grace_combine(None, None, None, 1, 1, 8, 1, None, None, None) == -1               # null pointers
     assert lib.grace_combine(None, None, None, 0, 1, 8, 1, None, None, None) == 0                # nothing to do
+    assert lib.grace_mfma_sustained(1, 1, None, None) == -1
 
 
 def test_workspace_bytes():
