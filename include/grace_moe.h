@@ -50,6 +50,12 @@ enum {
 
 typedef enum { GRACE_F32 = 0, GRACE_BF16 = 1 } grace_dtype;
 
+/* Replica selection policy (Section 4.3 of the paper describes both). */
+typedef enum {
+    GRACE_POLICY_TAR = 0, /* topology-aware routing with locality preference (Algorithm 4)            */
+    GRACE_POLICY_WRR = 1  /* weighted round-robin over all instances, no locality (Algorithm 3 alone) */
+} grace_policy;
+
 /* Limits checked by the entry points. */
 #define GRACE_MAX_EXPERTS 256   /* E                        */
 #define GRACE_MAX_TOPK 64       /* k                        */
@@ -123,7 +129,9 @@ size_t grace_workspace_bytes(int32_t T, int32_t E, int32_t k, int32_t I, int32_t
  * the candidate (ascending rank) whose cumulative polling-weight interval
  * contains c mod W, W = sum of the tier's polling weights (deterministic
  * weighted round-robin: over any W consecutive requests each candidate receives
- * exactly its weight).
+ * exactly its weight).  With GRACE_POLICY_WRR the candidate set is always "all
+ * instances" (the paper's first policy, which balances load but ignores
+ * locality); local_rank is then only range-checked.
  *
  * DEVICE: logits [T,E] fp32; rr_in [E] or NULL (= zeros); rr_out [E] or NULL,
  * receives (rr_in[e] + requests of e) mod W_e; topk_expert [T,k];
@@ -131,7 +139,7 @@ size_t grace_workspace_bytes(int32_t T, int32_t E, int32_t k, int32_t I, int32_t
  * requests per expert in this call; ws from grace_workspace_bytes.
  * Limits: 1 <= k <= min(E, GRACE_MAX_TOPK), E == table's E, T*k < 2^31, T >= 0.
  */
-int grace_route(const grace_table *table, int32_t local_rank, const float *logits, int32_t T, int32_t E, int32_t k,
+int grace_route(const grace_table *table, int32_t local_rank, grace_policy policy, const float *logits, int32_t T, int32_t E, int32_t k,
                 int32_t renorm, const uint32_t *rr_in, uint32_t *rr_out, int32_t *topk_expert, float *topk_weight,
                 int32_t *topk_inst, int32_t *expert_count, void *ws, void *stream);
 

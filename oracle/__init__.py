@@ -104,7 +104,7 @@ def instance_order(pl) -> InstanceOrder:
 
 # -- O2 + O3 -------------------------------------------------------------------
 def pick(topk_expert: np.ndarray, pl, local_rank: int, rr_in: Optional[np.ndarray] = None,
-         order: Optional[InstanceOrder] = None):
+         order: Optional[InstanceOrder] = None, policy: int = 0):
     """-> (topk_inst [T,k] dispatch-order ids, expert_count [E], rr_out [E])."""
     te = _i32(topk_expert)
     T, k = te.shape
@@ -117,7 +117,7 @@ def pick(topk_expert: np.ndarray, pl, local_rank: int, rr_in: Optional[np.ndarra
     cnt = np.empty(pl.E, dtype=np.int32)
     _check(lib().oracle_pick(_p(te), C.c_int32(T), C.c_int32(k), C.c_int32(pl.E), C.c_int32(pl.R),
                              _p(rank_node), _p(pw), _p(inst_ptr), _p(inst_rank), _p(order.csr_to_g),
-                             C.c_int32(local_rank), _p(rin), _p(rout), _p(ti), _p(cnt)), "pick")
+                             C.c_int32(local_rank), C.c_int32(policy), _p(rin), _p(rout), _p(ti), _p(cnt)), "pick")
     return ti, cnt, rout
 
 
@@ -207,10 +207,10 @@ class LayerResult:
     out: Optional[np.ndarray] = None        # [T, d] float64
 
 
-def route_permute(logits, pl, k: int, local_rank: int, renorm: int = 1, rr_in=None) -> LayerResult:
+def route_permute(logits, pl, k: int, local_rank: int, renorm: int = 1, rr_in=None, policy: int = 0) -> LayerResult:
     te, tw = topk(logits, k, renorm)
     order = instance_order(pl)
-    ti, cnt, rout = pick(te, pl, local_rank, rr_in, order)
+    ti, cnt, rout = pick(te, pl, local_rank, rr_in, order, policy)
     pm = permute(ti, pl, order)
     return LayerResult(te, tw, ti, cnt, rout, pm, order)
 

@@ -140,9 +140,12 @@ int oracle_instance_order(int32_t E, int32_t R, const int32_t *rank_node,
 int oracle_pick(const int32_t *topk_expert, int32_t T, int32_t k, int32_t E, int32_t R,
                 const int32_t *rank_node, const uint32_t *poll_weight,
                 const int32_t *inst_ptr, const int32_t *inst_rank, const int32_t *csr_to_g,
-                int32_t local_rank, const uint32_t *rr_in, uint32_t *rr_out,
+                int32_t local_rank, int32_t policy, const uint32_t *rr_in, uint32_t *rr_out,
                 int32_t *topk_inst, int32_t *expert_count)
 {
+    /* policy 0: topology-aware tiers (Algorithm 4); policy 1: all instances are candidates
+       (weighted round-robin alone, Section 4.3 first policy) */
+    if (policy != 0 && policy != 1) return ORACLE_EINVAL;
     if (local_rank < 0 || local_rank >= R) return ORACLE_EINVAL;
     uint64_t *cnt = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)E);
     int32_t *cand = (int32_t *)malloc(sizeof(int32_t) * (size_t)(R > 0 ? R : 1));
@@ -157,11 +160,13 @@ int oracle_pick(const int32_t *topk_expert, int32_t T, int32_t k, int32_t E, int
         expert_count[e] += 1;
         /* O3: build the tier's candidate list (CSR indices, ascending rank) */
         int32_t nc = 0;
-        for (int32_t i = inst_ptr[e]; i < inst_ptr[e + 1]; ++i)
-            if (inst_rank[i] == local_rank) cand[nc++] = i;
-        if (nc == 0)
+        if (policy == 0) {
             for (int32_t i = inst_ptr[e]; i < inst_ptr[e + 1]; ++i)
-                if (rank_node[inst_rank[i]] == my_node) cand[nc++] = i;
+                if (inst_rank[i] == local_rank) cand[nc++] = i;
+            if (nc == 0)
+                for (int32_t i = inst_ptr[e]; i < inst_ptr[e + 1]; ++i)
+                    if (rank_node[inst_rank[i]] == my_node) cand[nc++] = i;
+        }
         if (nc == 0)
             for (int32_t i = inst_ptr[e]; i < inst_ptr[e + 1]; ++i) cand[nc++] = i;
         if (nc == 0) { free(cnt); free(cand); return ORACLE_EINVAL; }
@@ -180,11 +185,13 @@ int oracle_pick(const int32_t *topk_expert, int32_t T, int32_t k, int32_t E, int
         for (int32_t e = 0; e < E; ++e) {
             /* tier weight sum of expert e as seen from local_rank */
             int32_t nc = 0;
-            for (int32_t i = inst_ptr[e]; i < inst_ptr[e + 1]; ++i)
-                if (inst_rank[i] == local_rank) cand[nc++] = i;
-            if (nc == 0)
+            if (policy == 0) {
                 for (int32_t i = inst_ptr[e]; i < inst_ptr[e + 1]; ++i)
-                    if (rank_node[inst_rank[i]] == my_node) cand[nc++] = i;
+                    if (inst_rank[i] == local_rank) cand[nc++] = i;
+                if (nc == 0)
+                    for (int32_t i = inst_ptr[e]; i < inst_ptr[e + 1]; ++i)
+                        if (rank_node[inst_rank[i]] == my_node) cand[nc++] = i;
+            }
             if (nc == 0)
                 for (int32_t i = inst_ptr[e]; i < inst_ptr[e + 1]; ++i) cand[nc++] = i;
             uint64_t W = 0;

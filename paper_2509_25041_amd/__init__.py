@@ -10,6 +10,8 @@ loaded, importing the binding's functions raises.
 from .binding import (  # noqa: F401
     GRACE_BF16,
     GRACE_F32,
+    GRACE_POLICY_TAR,
+    GRACE_POLICY_WRR,
     GraceError,
     GraceTable,
     grace_combine,

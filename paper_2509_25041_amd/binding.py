@@ -11,6 +11,7 @@ import torch
 from . import build as _build
 
 GRACE_F32, GRACE_BF16 = 0, 1
+GRACE_POLICY_TAR, GRACE_POLICY_WRR = 0, 1
 _STATUS = {0: "GRACE_OK", -1: "GRACE_EINVAL", -2: "GRACE_ESHAPE", -3: "GRACE_ETABLE", -4: "GRACE_ENOMEM",
            -5: "GRACE_EHIP"}
 
@@ -50,7 +51,7 @@ def load_library() -> C.CDLL:
     lib.grace_table_local_experts.argtypes = [vp, i32, vp, C.POINTER(i32)]
     lib.grace_workspace_bytes.restype = u64
     lib.grace_workspace_bytes.argtypes = [i32] * 7 + [C.c_int]
-    lib.grace_route.argtypes = [vp, i32, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.grace_route.argtypes = [vp, i32, C.c_int, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.grace_permute.argtypes = [vp, vp, i32, i32, vp, i32, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.grace_expert_ffn.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp, vp]
     lib.grace_expert_ffn_up.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp]
@@ -171,7 +172,7 @@ def _ws(ws: Optional[torch.Tensor], nbytes: int, device) -> torch.Tensor:
 
 def grace_route(table: GraceTable, local_rank: int, logits: torch.Tensor, k: int, renorm: int = 1,
                 rr_in: Optional[torch.Tensor] = None, rr_out: Optional[torch.Tensor] = None,
-                ws: Optional[torch.Tensor] = None, out=None):
+                ws: Optional[torch.Tensor] = None, out=None, policy: int = GRACE_POLICY_TAR):
     """-> (topk_expert [T,k] i32, topk_weight [T,k] f32, topk_inst [T,k] i32, expert_count [E] i32)."""
     T, E = logits.shape
     dev = logits.device
@@ -182,7 +183,7 @@ def grace_route(table: GraceTable, local_rank: int, logits: torch.Tensor, k: int
                torch.empty((T, k), dtype=torch.int32, device=dev), torch.empty((E,), dtype=torch.int32, device=dev))
     te, tw, ti, cnt = out
     ws = _ws(ws, grace_workspace_bytes(T, E, max(k, 1), table.I), dev)
-    _check(load_library().grace_route(table.handle, local_rank, _dp(logits), T, E, k, renorm, _dp(rr_in), _dp(rr_out),
+    _check(load_library().grace_route(table.handle, local_rank, policy, _dp(logits), T, E, k, renorm, _dp(rr_in), _dp(rr_out),
                                       _dp(te), _dp(tw), _dp(ti), _dp(cnt), _dp(ws), _stream()))
     return te, tw, ti, cnt
 

@@ -54,7 +54,7 @@ struct grace_table {
     // device side
     void *d_base = nullptr;
     // per (local_rank, expert): candidates of the tier Algorithm 4 selects
-    const int32_t *d_cand_ptr = nullptr;   // [R*E + 1]
+    const int32_t *d_cand_ptr = nullptr;   // [(R+1)*E + 1]; block R = all instances (no locality)
     const int32_t *d_cand_g = nullptr;     // instance id of each candidate, ascending rank
     const uint32_t *d_cand_cum = nullptr;  // inclusive cumulative polling weight inside the tier
     const int32_t *d_rank_ptr = nullptr;   // [R+1]

@@ -184,7 +184,7 @@ __global__ __launch_bounds__(64) void pick_kernel(const int32_t *__restrict__ to
 
 using namespace grace;
 
-extern "C" int grace_route(const grace_table *table, int32_t local_rank, const float *logits, int32_t T, int32_t E,
+extern "C" int grace_route(const grace_table *table, int32_t local_rank, grace_policy policy, const float *logits, int32_t T, int32_t E,
                            int32_t k, int32_t renorm, const uint32_t *rr_in, uint32_t *rr_out, int32_t *topk_expert,
                            float *topk_weight, int32_t *topk_inst, int32_t *expert_count, void *ws, void *stream) {
     if (!table) return fail(GRACE_EINVAL, "route: table is null");
@@ -194,6 +194,8 @@ extern "C" int grace_route(const grace_table *table, int32_t local_rank, const f
         return fail(GRACE_EINVAL, "route: k=%d outside [1, min(E=%d, %d)]", k, E, GRACE_MAX_TOPK);
     if (local_rank < 0 || local_rank >= table->R)
         return fail(GRACE_EINVAL, "route: local_rank=%d outside [0,%d)", local_rank, table->R);
+    if (policy != GRACE_POLICY_TAR && policy != GRACE_POLICY_WRR)
+        return fail(GRACE_EINVAL, "route: unknown policy %d", (int)policy);
     if ((int64_t)T * k > INT32_MAX) return fail(GRACE_ESHAPE, "route: T*k exceeds 2^31-1");
     if (!expert_count || !ws) return fail(GRACE_EINVAL, "route: expert_count or ws is null");
     if (T > 0 && (!logits || !topk_expert || !topk_weight || !topk_inst))
@@ -202,7 +204,7 @@ extern "C" int grace_route(const grace_table *table, int32_t local_rank, const f
     const int nchunks = (int)ceil_div(T, ROUTE_TOKENS_PER_CHUNK);
     int32_t *hist = (int32_t *)ws;
     int32_t *base = (int32_t *)((char *)ws + align_up((size_t)nchunks * E * 4, 256));
-    const int32_t *cand_ptr = table->d_cand_ptr + (size_t)local_rank * E;
+    const int32_t *cand_ptr = table->d_cand_ptr + (size_t)(policy == GRACE_POLICY_WRR ? table->R : local_rank) * E;
     if (nchunks > 0) {
         const int vpl = (E + 63) / 64;
         switch (vpl) {

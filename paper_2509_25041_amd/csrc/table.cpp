@@ -122,12 +122,18 @@ extern "C" int grace_table_create(grace_table **out, int32_t E, int32_t R, int32
     }
 
     // candidate tiers for every (local rank, expert)
-    std::vector<int32_t> cand_ptr((size_t)R * E + 1, 0), cand_g;
+    // block lr == R: all instances of the expert (policy without locality)
+    std::vector<int32_t> cand_ptr((size_t)(R + 1) * E + 1, 0), cand_g;
     std::vector<uint32_t> cand_cum;
     std::vector<int32_t> tier;
-    for (int32_t lr = 0; lr < R; ++lr)
+    for (int32_t lr = 0; lr <= R; ++lr)
         for (int32_t e = 0; e < E; ++e) {
-            tier_of(*t, lr, e, tier);
+            if (lr < R) {
+                tier_of(*t, lr, e, tier);
+            } else {
+                tier.clear();
+                for (int32_t i = inst_ptr[e]; i < inst_ptr[e + 1]; ++i) tier.push_back(i);
+            }
             uint32_t cum = 0;
             for (int32_t i : tier) {
                 cum += poll_weight[inst_rank[i]];

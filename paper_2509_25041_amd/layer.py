@@ -27,9 +27,10 @@ class GraceMoELayer:
 
     def __init__(self, table: GraceTable, local_rank: int, T: int, k: int, d: int, f: int, dtype: torch.dtype,
                  w_gate: torch.Tensor, w_up: torch.Tensor, w_down: torch.Tensor, shared=None, renorm: int = 1,
-                 device="cuda"):
+                 device="cuda", policy: int = 0):
         self.table, self.local_rank, self.T, self.k, self.d, self.f = table, local_rank, T, k, d, f
         self.renorm = renorm
+        self.policy = policy
         self.w = (w_gate, w_up, w_down)
         self.shared = shared
         self.n_shared = 0 if shared is None else shared[0].shape[0]
@@ -77,7 +78,7 @@ class GraceMoELayer:
         S = wg.shape[0]
         ws = p(self.ws)
         calls = [
-            ("route", lib.grace_route, (h, lr, p(logits), T, self.table.E, k, self.renorm, p(rr_in), p(rr_out), p(te),
+            ("route", lib.grace_route, (h, lr, self.policy, p(logits), T, self.table.E, k, self.renorm, p(rr_in), p(rr_out), p(te),
                                         p(tw), p(ti), p(cnt), ws, st)),
             ("permute", lib.grace_permute, (h, p(ti), T, k, p(x), d, dt, p(pos), p(src), p(ioff), p(roff), p(noff),
                                             p(self.xp), ws, st)),

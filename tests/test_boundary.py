@@ -66,7 +66,7 @@ def test_null_and_range_checks_without_device():
     assert lib.grace_table_destroy(None) == 0
     assert lib.grace_table_info(None, None, None, None, None, None) == -1
     # compute entry points refuse a null table before touching the device
-    assert lib.grace_route(None, 0, None, 1, 1, 1, 1, None, None, None, None, None, None, None, None) == -1
+    assert lib.grace_route(None, 0, 0, None, 1, 1, 1, 1, None, None, None, None, None, None, None, None) == -1
     assert lib.grace_permute(None, None, 1, 1, None, 8, 1, None, None, None, None, None, None, None, None) == -1
     assert lib.grace_expert_ffn(None, 0, None, None, 1, 1, 8, 8, 1, None, None, None, None, None, None) == -1
     assert lib.grace_shared_ffn(None, 1, 8, 8, 0, 1, None, None, None, None, None, None) == -1

@@ -46,12 +46,12 @@ def _need_gpu():
     grace.load_library()
 
 
-def run_route_permute(wl, pl, k, local_rank, rr_in=None, renorm=1, with_rows=True):
+def run_route_permute(wl, pl, k, local_rank, rr_in=None, renorm=1, with_rows=True, policy=0):
     table = grace.GraceTable.from_placement(pl)
     logits = dev(wl.logits)
     rin = None if rr_in is None else torch.from_numpy(rr_in.view(np.int32)).cuda()
     rout = torch.empty(pl.E, dtype=torch.int32, device="cuda")
-    te, tw, ti, cnt = grace.grace_route(table, local_rank, logits, k, renorm, rin, rout)
+    te, tw, ti, cnt = grace.grace_route(table, local_rank, logits, k, renorm, rin, rout, policy=policy)
     x = dev(wl.x) if with_rows else None
     pos, src, ioff, roff, noff, xp = grace.grace_permute(table, ti, x)
     torch.cuda.synchronize()
@@ -99,6 +99,19 @@ def test_route_rr_carry_and_no_renorm():
     ref = oracle.route_permute(wl.logits, wl.placement, cfg.k, 9, renorm=0, rr_in=rr_in)
     _, g = run_route_permute(wl, wl.placement, cfg.k, 9, rr_in=rr_in, renorm=0, with_rows=False)
     check_route_permute(g, ref, wl, cfg.k)
+
+
+@pytest.mark.parametrize("name,local_rank", [("olmoe", 0), ("dsv2lite", 21), ("mixtral", 6)])
+def test_route_wrr_policy_without_locality(name, local_rank):
+    """The paper's first policy (weighted round-robin over all instances): bit-exact, and
+    independent of the source rank."""
+    cfg = CONFIGS[name]
+    wl = make_workload(cfg, T=min(cfg.T, 6000))
+    ref = oracle.route_permute(wl.logits, wl.placement, cfg.k, local_rank, policy=1)
+    _, g = run_route_permute(wl, wl.placement, cfg.k, local_rank, with_rows=False, policy=grace.GRACE_POLICY_WRR)
+    check_route_permute(g, ref, wl, cfg.k)
+    _, g0 = run_route_permute(wl, wl.placement, cfg.k, 0, with_rows=False, policy=grace.GRACE_POLICY_WRR)
+    np.testing.assert_array_equal(host(g0.ti), host(g.ti))
 
 
 @pytest.mark.parametrize("E,k,T", [(128, 8, 1500), (200, 5, 700), (256, 64, 300), (8, 8, 100), (3, 1, 129)])

@@ -112,6 +112,15 @@ def test_pick_and_permute_worked_example():
     assert ti.reshape(-1).tolist() == c["topk_inst"]
     assert cnt.tolist() == c["expert_count"]
     assert rout.tolist() == c["rr_out"]
+    c = g["case_wrr_policy"]
+    for lr in (c["local_rank"], 0, 5):                  # without locality the source rank does not matter
+        ti, cnt, rout = oracle.pick(te, pl, lr, policy=1)
+        assert ti.reshape(-1).tolist() == c["topk_inst"]
+        assert cnt.tolist() == c["expert_count"]
+        assert rout.tolist() == c["rr_out"]
+    ti_tar, _, _ = oracle.pick(te, pl, c["local_rank"], policy=0)
+    assert order.g_rank[ti_tar.reshape(-1)[5]] == c["local_rank"]      # Algorithm 4 keeps expert 0 on rank 3
+    assert ti_tar.reshape(-1).tolist() != c["topk_inst"]
 
 
 # --------------------------------------------------------- O3 invariants --
@@ -123,13 +132,19 @@ def _cands(pl, e, local_rank):
     return same if same else ranks
 
 
+def _cands_policy(pl, e, local_rank, policy):
+    if policy == 1:
+        return pl.inst_rank[pl.inst_ptr[e]:pl.inst_ptr[e + 1]].tolist()
+    return _cands(pl, e, local_rank)
+
+
 @pytest.mark.parametrize("name", ["tiny", "olmoe", "qwen", "dsv2lite", "mixtral"])
-@pytest.mark.parametrize("local_rank", [0, 3])
-def test_pick_invariants_and_wrr_shares(name, local_rank):
+@pytest.mark.parametrize("local_rank,policy", [(0, 0), (3, 0), (1, 1)])
+def test_pick_invariants_and_wrr_shares(name, local_rank, policy):
     cfg = CONFIGS[name]
     wl = make_workload(cfg, T=min(cfg.T, 2048))
     pl = wl.placement
-    res = oracle.route_permute(wl.logits, pl, cfg.k, local_rank)
+    res = oracle.route_permute(wl.logits, pl, cfg.k, local_rank, policy=policy)
     order = res.order
     ti = res.topk_inst.reshape(-1)
     te = res.topk_expert.reshape(-1)
@@ -143,9 +158,11 @@ def test_pick_invariants_and_wrr_shares(name, local_rank):
     for e in range(cfg.E):
         m = te == e
         n = int(m.sum())
-        cands = _cands(pl, e, local_rank)
+        cands = _cands_policy(pl, e, local_rank, policy)
         ranks_e = pl.inst_rank[pl.inst_ptr[e]:pl.inst_ptr[e + 1]].tolist()
-        if local_rank in ranks_e:                      # tier 1: never leaves the GPU
+        if policy == 1:
+            pass
+        elif local_rank in ranks_e:                      # tier 1: never leaves the GPU
             assert (chosen_rank[m] == local_rank).all()
         elif any(pl.rank_node[r] == my_node for r in ranks_e):   # tier 2: never leaves the node
             assert (pl.rank_node[chosen_rank[m]] == my_node).all()
