@@ -276,6 +276,29 @@ def test_layer_object_rank_share_matches_oracle():
     assert rel_err(oracle.widen(host(out)), out_ref) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("name", ["olmoe_decode64", "olmoe_decode512"])
+def test_decode_shaped_rank_share_element_by_element(name):
+    """Decode-sized batches (every instance far below a tile): whole rank share, every element."""
+    cfg = CONFIGS[name]
+    wl = make_workload(cfg)
+    pl = wl.placement
+    lr = cfg.local_rank
+    table = grace.GraceTable.from_placement(pl)
+    wg, wu, wd = _stack_dev(wl, table.local_experts(lr))
+    layer = grace.GraceMoELayer(table, lr, cfg.T, cfg.k, cfg.d, cfg.f, torch.bfloat16, wg, wu, wd)
+    out = layer.forward(dev(wl.logits), dev(wl.x))
+    torch.cuda.synchronize()
+    ref = oracle.route_permute(wl.logits, pl, cfg.k, lr)
+    np.testing.assert_array_equal(host(layer.route_out[2]), ref.topk_inst)
+    np.testing.assert_array_equal(host(layer.perm_out[0]), ref.perm.perm_pos)
+    np.testing.assert_array_equal(host(layer.perm_out[2]), ref.perm.inst_off)
+    x64 = oracle.widen(wl.x)
+    y_ref = oracle.expert_ffn(ref, x64, cfg.k, [lr], _weights64(wl), threads=8)
+    assert rel_err(oracle.widen(host(layer.y)), y_ref) <= TOL["bf16"]
+    out_ref = oracle.combine(y_ref, ref.perm.perm_pos, ref.topk_weight)
+    assert rel_err(oracle.widen(host(out)), out_ref) <= TOL["bf16"]
+
+
 def test_graph_replays_match_eager():
     """A captured step replayed several times, with eager work and synchronisations in
     between and inputs changed in place, gives the eager result every time."""

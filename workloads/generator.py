@@ -74,6 +74,12 @@ CONFIGS: Dict[str, LayerConfig] = {
                            nodes=2, gpus_per_node=4, n_hot=2, replica_mode="per_node", seed=2),
     "qwen": LayerConfig("qwen", T=16384, E=60, k=4, d=2048, f=1408, dtype="bf16", zipf_s=1.5,
                         nodes=4, gpus_per_node=2, n_hot=6, replica_mode="eq3", n_shared=4, seed=3),
+    # decode-shaped steps (Section 6.1 workloads: batch 256 / 512 over 4-8 GPUs per decode step;
+    # Appendix A.4: lighter batches 64 / 128): a few dozen to a few hundred tokens per rank
+    "olmoe_decode64": LayerConfig("olmoe_decode64", T=64, E=64, k=8, d=2048, f=1024, dtype="bf16", zipf_s=1.2,
+                                  nodes=2, gpus_per_node=2, n_hot=4, replica_mode="all", seed=5),
+    "olmoe_decode512": LayerConfig("olmoe_decode512", T=512, E=64, k=8, d=2048, f=1024, dtype="bf16", zipf_s=1.2,
+                                   nodes=2, gpus_per_node=2, n_hot=4, replica_mode="all", seed=6),
     "dsv2lite": LayerConfig("dsv2lite", T=32768, E=64, k=6, d=2048, f=1408, dtype="bf16", zipf_s=1.2,
                             nodes=4, gpus_per_node=8, n_hot=8, replica_mode="per_node", n_shared=2,
                             drift_block=4096, seed=4),
