@@ -161,6 +161,30 @@ int grace_permute(const grace_table *table, const int32_t *topk_inst, int32_t T,
                   grace_dtype dt, int32_t *perm_pos, int32_t *perm_src, int32_t *inst_off, int32_t *rank_off,
                   int32_t *node_off, void *xp, void *ws, void *stream);
 
+/* ---- grace_send_lists: de-duplicated hierarchical send lists ------------------
+ * Section 5: a token routed to several experts on the same destination is
+ * transmitted only once.  For the T tokens of local_rank and their instance ids
+ * (from grace_route) this builds
+ *   rank_send_ptr [R+1], rank_send_tok : for every destination rank the ascending list of
+ *       distinct tokens with at least one assignment there (what stage 2 delivers to it);
+ *   node_send_ptr [N+1], node_send_tok : the same per destination node (what stage 1 sends);
+ *   expand [T*k] : for assignment a, the index of its token inside the send list of its
+ *       destination rank, so the receiver can expand the unique rows to one row per
+ *       assignment (row of assignment a = received row expand[a]);
+ *   traffic [4] (int64, may be NULL) in tokens: [0] cross-node with de-duplication (sum over
+ *       other nodes of their distinct tokens), [1] cross-node without (one row per assignment),
+ *       [2] intra-node with de-duplication (distinct tokens for the other ranks of the own node,
+ *       plus in every other node for the ranks other than the stage-1 peer, i.e. the rank with
+ *       local_rank's index inside that node), [3] intra-node rows of a flat dispatch
+ *       (assignments to the other ranks of the own node).
+ * DEVICE: topk_inst [T*k]; the two token arrays and expand hold T*k entries (at most
+ * T*min(k, R) resp. T*min(k, N) are written); ws from grace_workspace_bytes.
+ * The dispatch permutation of grace_permute is unaffected (one row per assignment).
+ */
+int grace_send_lists(const grace_table *table, int32_t local_rank, const int32_t *topk_inst, int32_t T, int32_t k,
+                     int32_t *rank_send_ptr, int32_t *rank_send_tok, int32_t *node_send_ptr, int32_t *node_send_tok,
+                     int32_t *expand, int64_t *traffic, void *ws, void *stream);
+
 /* ---- grace_expert_ffn: grouped SwiGLU FFN over one rank's rows ---------------
  * The expert computation between dispatch and aggregation (Section 1).  For
  * every instance i hosted by `rank` (slot s, expert e) and every buffer row p

@@ -40,7 +40,7 @@ def lib() -> C.CDLL:
         build()
         _lib = C.CDLL(_SO)
         for name in ("oracle_topk", "oracle_instance_order", "oracle_pick", "oracle_permute",
-                     "oracle_gather_rows", "oracle_ffn_rows", "oracle_combine", "oracle_max_threads"):
+                     "oracle_gather_rows", "oracle_ffn_rows", "oracle_combine", "oracle_send_lists", "oracle_max_threads"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -152,6 +152,36 @@ def gather_rows(x: np.ndarray, perm_src: np.ndarray, k: int) -> np.ndarray:
     out = np.empty((src.shape[0], x.shape[1]), dtype=x.dtype)
     _check(lib().oracle_gather_rows(_p(x), C.c_int64(x.shape[1] * x.itemsize), _p(src),
                                     C.c_int64(src.shape[0]), C.c_int32(k), _p(out)), "gather_rows")
+    return out
+
+
+# -- send lists -----------------------------------------------------------------
+@dataclass
+class SendLists:
+    rank_send_ptr: np.ndarray   # [R+1]
+    rank_send_tok: np.ndarray   # [rank_send_ptr[R]]
+    node_send_ptr: np.ndarray   # [N+1]
+    node_send_tok: np.ndarray   # [node_send_ptr[N]]
+    expand: np.ndarray          # [T*k]
+    traffic: np.ndarray         # [4] int64
+
+
+def send_lists(topk_inst: np.ndarray, pl, local_rank: int, order: Optional[InstanceOrder] = None) -> SendLists:
+    ti = _i32(topk_inst)
+    T, k = ti.shape
+    order = order or instance_order(pl)
+    rank_node = _i32(pl.rank_node)
+    n = T * k
+    out = SendLists(np.empty(pl.R + 1, np.int32), np.empty(max(n, 1), np.int32), np.empty(pl.N + 1, np.int32),
+                    np.empty(max(n, 1), np.int32), np.empty(max(n, 1), np.int32), np.empty(4, np.int64))
+    _check(lib().oracle_send_lists(_p(ti), C.c_int32(T), C.c_int32(k), C.c_int32(int(pl.inst_ptr[-1])),
+                                   C.c_int32(pl.R), C.c_int32(pl.N), _p(order.g_rank), _p(rank_node),
+                                   C.c_int32(local_rank), _p(out.rank_send_ptr), _p(out.rank_send_tok),
+                                   _p(out.node_send_ptr), _p(out.node_send_tok), _p(out.expand), _p(out.traffic)),
+           "send_lists")
+    out.rank_send_tok = out.rank_send_tok[:out.rank_send_ptr[-1]]
+    out.node_send_tok = out.node_send_tok[:out.node_send_ptr[-1]]
+    out.expand = out.expand[:n]
     return out
 
 

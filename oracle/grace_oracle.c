@@ -306,6 +306,78 @@ int oracle_combine(const double *y, const int32_t *perm_pos, const float *topk_w
     return ORACLE_OK;
 }
 
+/* ------------------------------------------------------------ send lists --
+ * Section 5: a token with several experts on one destination is transmitted
+ * once.  For every destination rank (node): the ascending list of tokens that
+ * have at least one assignment there.  expand[a] = index of a's token in the
+ * list of a's destination rank.  traffic (tokens): [0] cross-node with
+ * de-duplication, [1] cross-node one row per assignment, [2] intra-node with
+ * de-duplication (other ranks of the own node, plus in every other node the
+ * ranks other than the stage-1 peer = the rank with local_rank's index inside
+ * that node), [3] intra-node rows of a flat dispatch (assignments to the other
+ * ranks of the own node).
+ */
+int oracle_send_lists(const int32_t *topk_inst, int32_t T, int32_t k, int32_t I, int32_t R, int32_t N,
+                      const int32_t *g_rank, const int32_t *rank_node, int32_t local_rank,
+                      int32_t *rank_send_ptr, int32_t *rank_send_tok, int32_t *node_send_ptr,
+                      int32_t *node_send_tok, int32_t *expand, int64_t *traffic)
+{
+    if (local_rank < 0 || local_rank >= R) return ORACLE_EINVAL;
+    for (int64_t a = 0; a < (int64_t)T * k; ++a)
+        if (topk_inst[a] < 0 || topk_inst[a] >= I) return ORACLE_EINVAL;
+    int32_t p = 0;
+    for (int32_t r = 0; r < R; ++r) {
+        rank_send_ptr[r] = p;
+        for (int32_t t = 0; t < T; ++t) {
+            int hit = 0;
+            for (int32_t j = 0; j < k; ++j) if (g_rank[topk_inst[(int64_t)t * k + j]] == r) hit = 1;
+            if (hit) {
+                for (int32_t j = 0; j < k; ++j)
+                    if (g_rank[topk_inst[(int64_t)t * k + j]] == r) expand[(int64_t)t * k + j] = p - rank_send_ptr[r];
+                rank_send_tok[p++] = t;
+            }
+        }
+    }
+    rank_send_ptr[R] = p;
+    p = 0;
+    for (int32_t n = 0; n < N; ++n) {
+        node_send_ptr[n] = p;
+        for (int32_t t = 0; t < T; ++t) {
+            int hit = 0;
+            for (int32_t j = 0; j < k; ++j) if (rank_node[g_rank[topk_inst[(int64_t)t * k + j]]] == n) hit = 1;
+            if (hit) node_send_tok[p++] = t;
+        }
+    }
+    node_send_ptr[N] = p;
+    if (traffic) {
+        const int32_t my_node = rank_node[local_rank];
+        int32_t my_first = 0;
+        while (rank_node[my_first] != my_node) ++my_first;
+        const int32_t local_idx = local_rank - my_first;
+        traffic[0] = traffic[1] = traffic[2] = traffic[3] = 0;
+        for (int32_t n = 0; n < N; ++n)
+            if (n != my_node) traffic[0] += node_send_ptr[n + 1] - node_send_ptr[n];
+        for (int64_t a = 0; a < (int64_t)T * k; ++a) {
+            const int32_t r = g_rank[topk_inst[a]];
+            if (rank_node[r] != my_node) traffic[1] += 1;
+            else if (r != local_rank) traffic[3] += 1;
+        }
+        for (int32_t r = 0; r < R; ++r) {
+            const int32_t nd = rank_node[r];
+            const int32_t uniq = rank_send_ptr[r + 1] - rank_send_ptr[r];
+            if (nd == my_node) {
+                if (r != local_rank) traffic[2] += uniq;
+            } else {
+                int32_t first = 0, size = 0;
+                while (rank_node[first] != nd) ++first;
+                while (first + size < R && rank_node[first + size] == nd) ++size;
+                if (r != first + local_idx % size) traffic[2] += uniq;
+            }
+        }
+    }
+    return ORACLE_OK;
+}
+
 int oracle_max_threads(void)
 {
 #ifdef _OPENMP

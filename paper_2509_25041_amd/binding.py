@@ -17,7 +17,7 @@ _STATUS = {0: "GRACE_OK", -1: "GRACE_EINVAL", -2: "GRACE_ESHAPE", -3: "GRACE_ETA
 
 EXPORTS = ("grace_table_validate", "grace_table_create", "grace_table_destroy", "grace_table_info",
            "grace_table_instances", "grace_table_local_experts", "grace_workspace_bytes", "grace_route",
-           "grace_permute", "grace_expert_ffn", "grace_expert_ffn_up", "grace_expert_ffn_down", "grace_shared_ffn", "grace_combine", "grace_mfma_sustained", "grace_last_error")
+           "grace_permute", "grace_send_lists", "grace_expert_ffn", "grace_expert_ffn_up", "grace_expert_ffn_down", "grace_shared_ffn", "grace_combine", "grace_mfma_sustained", "grace_last_error")
 
 _lib: Optional[C.CDLL] = None
 
@@ -53,6 +53,7 @@ def load_library() -> C.CDLL:
     lib.grace_workspace_bytes.argtypes = [i32] * 7 + [C.c_int]
     lib.grace_route.argtypes = [vp, i32, C.c_int, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.grace_permute.argtypes = [vp, vp, i32, i32, vp, i32, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.grace_send_lists.argtypes = [vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.grace_expert_ffn.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp, vp]
     lib.grace_expert_ffn_up.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp]
     lib.grace_expert_ffn_down.argtypes = [vp, i32, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp]
@@ -207,6 +208,22 @@ def grace_permute(table: GraceTable, topk_inst: torch.Tensor, x: Optional[torch.
     _check(load_library().grace_permute(table.handle, _dp(topk_inst), T, k, _dp(x), d, dt, _dp(pos), _dp(src), _dp(ioff),
                                         _dp(roff), _dp(noff), _dp(xp) if x is not None else None, _dp(ws), _stream()))
     return pos, src, ioff, roff, noff, xp
+
+
+def grace_send_lists(table: GraceTable, local_rank: int, topk_inst: torch.Tensor, ws: Optional[torch.Tensor] = None):
+    """-> (rank_send_ptr [R+1], rank_send_tok [T*k], node_send_ptr [N+1], node_send_tok [T*k], expand [T*k],
+    traffic [4] int64); see grace_moe.h."""
+    T, k = topk_inst.shape
+    dev = topk_inst.device
+    i32 = dict(dtype=torch.int32, device=dev)
+    rp, rt = torch.empty(table.R + 1, **i32), torch.full((T * k,), -1, **i32)
+    np_, nt = torch.empty(table.N + 1, **i32), torch.full((T * k,), -1, **i32)
+    ex = torch.empty(T * k, **i32)
+    tr = torch.empty(4, dtype=torch.int64, device=dev)
+    ws = _ws(ws, grace_workspace_bytes(T, table.E, k, table.I), dev)
+    _check(load_library().grace_send_lists(table.handle, local_rank, _dp(topk_inst), T, k, _dp(rp), _dp(rt), _dp(np_),
+                                           _dp(nt), _dp(ex), _dp(tr), _dp(ws), _stream()))
+    return rp, rt, np_, nt, ex, tr
 
 
 def grace_expert_ffn(table: GraceTable, rank: int, xp: torch.Tensor, inst_off: torch.Tensor, T: int, k: int,

@@ -59,4 +59,6 @@ struct grace_table {
     const uint32_t *d_cand_cum = nullptr;  // inclusive cumulative polling weight inside the tier
     const int32_t *d_rank_ptr = nullptr;   // [R+1]
     const int32_t *d_node_first_inst = nullptr;  // [N+1] first instance id of each node (I at the end)
+    const int32_t *d_inst_rank = nullptr;        // [I] hosting rank of each instance id
+    const int32_t *d_rank_node = nullptr;        // [R]
 };

@@ -1,0 +1,172 @@
+// grace_send_lists: de-duplicated hierarchical send lists and traffic counters.
+//
+// The two-stage dispatch of Section 5 forwards a token once per destination even
+// when several of its experts live there ("tokens routed to multiple experts on
+// the same destination are transmitted only once").  For the tokens of
+// local_rank this builds, per destination rank and per destination node, the
+// ascending list of distinct tokens that have at least one assignment there, the
+// map that lets the receiver expand the unique rows back to one row per
+// assignment, and the token counts the paper's traffic metrics are made of.
+//
+//   1. dedup_keys_kernel  one lane per token: destination rank / node of each of
+//                         its k assignments; the first assignment per destination
+//                         keeps the destination as its sort key, the others get -1
+//   2. stable counting sort by rank key and by node key (stable_sort.h)
+//   3. expand_traffic_kernel  expansion map + traffic sums
+#include "common.h"
+#include "stable_sort.h"
+
+namespace grace {
+
+__global__ __launch_bounds__(256) void dedup_keys_kernel(const int32_t *__restrict__ topk_inst, int T, int k, int I,
+                                                         const int32_t *__restrict__ inst_rank,
+                                                         const int32_t *__restrict__ rank_node,
+                                                         int32_t *__restrict__ rank_key, int32_t *__restrict__ node_key,
+                                                         int32_t *__restrict__ first_idx) {
+    const int t = (int)(blockIdx.x * 256 + threadIdx.x);
+    if (t >= T) return;
+    const int32_t *row = topk_inst + (size_t)t * k;
+    for (int j = 0; j < k; ++j) {
+        const int g = row[j];
+        const size_t a = (size_t)t * k + j;
+        if ((unsigned)g >= (unsigned)I) {  // id outside the table: no destination
+            rank_key[a] = -1; node_key[a] = -1; first_idx[a] = -1;
+            continue;
+        }
+        const int r = inst_rank[g], nd = rank_node[r];
+        int first_r = j;
+        bool first_n = true;
+        for (int jj = 0; jj < j; ++jj) {
+            const int g2 = row[jj];
+            if ((unsigned)g2 >= (unsigned)I) continue;
+            const int r2 = inst_rank[g2];
+            if (r2 == r && first_r == j) first_r = jj;
+            if (rank_node[r2] == nd) first_n = false;
+        }
+        rank_key[a] = (first_r == j) ? r : -1;
+        node_key[a] = first_n ? nd : -1;
+        first_idx[a] = t * k + first_r;
+    }
+}
+
+// expand[a] = index of a's token in the send list of a's destination rank.
+// traffic[0] cross-node tokens with de-duplication: sum over other nodes of their distinct tokens
+// traffic[1] cross-node rows without (one per assignment)
+// traffic[2] intra-node tokens with de-duplication: distinct tokens for the other ranks of the own
+//            node plus, in every other node, for the ranks other than the peer that received stage 1
+// traffic[3] intra-node rows of a flat dispatch: assignments to the other ranks of the own node
+__global__ __launch_bounds__(256) void expand_traffic_kernel(const int32_t *__restrict__ topk_inst, int64_t n_assign, int I,
+                                                             int R, int N, int local_rank,
+                                                             const int32_t *__restrict__ inst_rank,
+                                                             const int32_t *__restrict__ rank_node,
+                                                             const int32_t *__restrict__ first_idx,
+                                                             const int32_t *__restrict__ send_pos,
+                                                             const int32_t *__restrict__ rank_send_ptr,
+                                                             const int32_t *__restrict__ node_send_ptr,
+                                                             int32_t *__restrict__ expand, int64_t *__restrict__ traffic) {
+    const int64_t a = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (a < n_assign) {
+        const int g = topk_inst[a];
+        int32_t e = -1;
+        if ((unsigned)g < (unsigned)I) e = send_pos[first_idx[a]] - rank_send_ptr[inst_rank[g]];
+        expand[a] = e;
+    }
+    if (!traffic || blockIdx.x != 0) return;
+    // rows per rank without de-duplication
+    __shared__ unsigned long long acc[4];
+    __shared__ int32_t naive_rank[GRACE_MAX_RANKS];
+    if (threadIdx.x < 4) acc[threadIdx.x] = 0ull;
+    for (int r = (int)threadIdx.x; r < R; r += 256) naive_rank[r] = 0;
+    __syncthreads();
+    for (int64_t i = threadIdx.x; i < n_assign; i += 256) {
+        const int g = topk_inst[i];
+        if ((unsigned)g < (unsigned)I) atomicAdd(&naive_rank[inst_rank[g]], 1);
+    }
+    __syncthreads();
+    const int my_node = rank_node[local_rank];
+    int my_first = 0;  // first rank of the own node (ranks are node-major)
+    while (my_first < R && rank_node[my_first] != my_node) ++my_first;
+    const int local_idx = local_rank - my_first;
+    for (int r = (int)threadIdx.x; r < R; r += 256) {
+        const int nd = rank_node[r];
+        const unsigned long long uniq = (unsigned long long)(rank_send_ptr[r + 1] - rank_send_ptr[r]);
+        const unsigned long long rows = (unsigned long long)naive_rank[r];
+        if (nd != my_node) {
+            atomicAdd(&acc[1], rows);
+            // the peer of local_rank in node nd: same index inside the node (modulo the node's size)
+            int first = r, size = 0;
+            while (first > 0 && rank_node[first - 1] == nd) --first;
+            while (first + size < R && rank_node[first + size] == nd) ++size;
+            const int peer = first + local_idx % size;
+            if (r != peer) atomicAdd(&acc[2], uniq);
+        } else if (r != local_rank) {
+            atomicAdd(&acc[2], uniq);
+            atomicAdd(&acc[3], rows);
+        }
+    }
+    for (int n = (int)threadIdx.x; n < N; n += 256)
+        if (n != my_node) atomicAdd(&acc[0], (unsigned long long)(node_send_ptr[n + 1] - node_send_ptr[n]));
+    __syncthreads();
+    if (threadIdx.x < 4) traffic[threadIdx.x] = (int64_t)acc[threadIdx.x];
+}
+
+static int sort_by_key(const int32_t *keys, int64_t n, int k, int nkeys, int32_t *hist, int32_t *base, int32_t *off,
+                       int32_t *pos, int32_t *tok, hipStream_t st) {
+    const int nchunks = (int)ceil_div(n, PERM_CHUNK);
+    int nbits = 0;
+    while ((1 << nbits) < nkeys) ++nbits;
+    if (nchunks > 0) {
+        key_hist_kernel<<<nchunks, 64, 0, st>>>(keys, n, nkeys, hist);
+        GRACE_LAUNCH_CHECK("key_hist_kernel");
+    }
+    key_scan_kernel<<<1, SCAN_THREADS, 0, st>>>(hist, base, nchunks, nkeys, 0, 0, nullptr, nullptr, off, nullptr, nullptr);
+    GRACE_LAUNCH_CHECK("key_scan_kernel");
+    if (nchunks > 0) {
+        key_pos_kernel<<<nchunks, 64, 0, st>>>(keys, n, nkeys, base, off, pos, tok, nbits, k);
+        GRACE_LAUNCH_CHECK("key_pos_kernel");
+    }
+    return GRACE_OK;
+}
+
+}  // namespace grace
+
+using namespace grace;
+
+extern "C" int grace_send_lists(const grace_table *table, int32_t local_rank, const int32_t *topk_inst, int32_t T,
+                                int32_t k, int32_t *rank_send_ptr, int32_t *rank_send_tok, int32_t *node_send_ptr,
+                                int32_t *node_send_tok, int32_t *expand, int64_t *traffic, void *ws, void *stream) {
+    if (!table) return fail(GRACE_EINVAL, "send_lists: table is null");
+    if (local_rank < 0 || local_rank >= table->R)
+        return fail(GRACE_EINVAL, "send_lists: local_rank=%d outside [0,%d)", local_rank, table->R);
+    if (T < 0 || k < 1) return fail(GRACE_EINVAL, "send_lists: T=%d, k=%d invalid", T, k);
+    if ((int64_t)T * k > INT32_MAX) return fail(GRACE_ESHAPE, "send_lists: T*k exceeds 2^31-1");
+    if (!rank_send_ptr || !node_send_ptr || !ws) return fail(GRACE_EINVAL, "send_lists: null offset or ws pointer");
+    if (T > 0 && (!topk_inst || !rank_send_tok || !node_send_tok || !expand))
+        return fail(GRACE_EINVAL, "send_lists: null device pointer");
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t n = (int64_t)T * k;
+    const int R = table->R, N = table->N, I = table->I;
+    const size_t seg = align_up((size_t)n * 4, 256);
+    char *w = (char *)ws;
+    int32_t *rank_key = (int32_t *)w, *node_key = (int32_t *)(w + seg), *first_idx = (int32_t *)(w + 2 * seg);
+    int32_t *pos_r = (int32_t *)(w + 3 * seg), *pos_n = (int32_t *)(w + 4 * seg);
+    const size_t nchunks = (size_t)ceil_div(n, PERM_CHUNK);
+    int32_t *hist = (int32_t *)(w + 5 * seg);
+    int32_t *base = (int32_t *)(w + 5 * seg + align_up(nchunks * (size_t)GRACE_MAX_RANKS * 4, 256));
+    if (T > 0) {
+        dedup_keys_kernel<<<(unsigned)ceil_div(T, 256), 256, 0, st>>>(topk_inst, T, k, I, table->d_inst_rank,
+                                                                     table->d_rank_node, rank_key, node_key, first_idx);
+        GRACE_LAUNCH_CHECK("dedup_keys_kernel");
+    }
+    int rc = sort_by_key(rank_key, n, k, R, hist, base, rank_send_ptr, pos_r, rank_send_tok, st);
+    if (rc != GRACE_OK) return rc;
+    rc = sort_by_key(node_key, n, k, N, hist, base, node_send_ptr, pos_n, node_send_tok, st);
+    if (rc != GRACE_OK) return rc;
+    if (n > 0 || traffic) {
+        expand_traffic_kernel<<<(unsigned)std::max<int64_t>(1, ceil_div(n, 256)), 256, 0, st>>>(
+            topk_inst, n, I, R, N, local_rank, table->d_inst_rank, table->d_rank_node, first_idx, pos_r, rank_send_ptr,
+            node_send_ptr, expand, traffic);
+        GRACE_LAUNCH_CHECK("expand_traffic_kernel");
+    }
+    return GRACE_OK;
+}

@@ -150,13 +150,17 @@ extern "C" int grace_table_create(grace_table **out, int32_t E, int32_t R, int32
     const size_t o_cum = o_g + al(cand_g.size() * 4);
     const size_t o_rank = o_cum + al(cand_cum.size() * 4);
     const size_t o_node = o_rank + al((size_t)(R + 1) * 4);
-    const size_t total = o_node + al((size_t)(N + 1) * 4);
+    const size_t o_irank = o_node + al((size_t)(N + 1) * 4);
+    const size_t o_rnode = o_irank + al((size_t)I * 4);
+    const size_t total = o_rnode + al((size_t)R * 4);
     std::vector<char> stage(total, 0);
     memcpy(stage.data() + o_ptr, cand_ptr.data(), cand_ptr.size() * 4);
     memcpy(stage.data() + o_g, cand_g.data(), cand_g.size() * 4);
     memcpy(stage.data() + o_cum, cand_cum.data(), cand_cum.size() * 4);
     memcpy(stage.data() + o_rank, t->rank_ptr.data(), (size_t)(R + 1) * 4);
     memcpy(stage.data() + o_node, node_first_inst.data(), (size_t)(N + 1) * 4);
+    memcpy(stage.data() + o_irank, t->g_rank.data(), (size_t)I * 4);
+    memcpy(stage.data() + o_rnode, rank_node, (size_t)R * 4);
 
     hipError_t he = hipGetDevice(&t->device);
     if (he == hipSuccess) he = hipMalloc(&t->d_base, total);
@@ -173,6 +177,8 @@ extern "C" int grace_table_create(grace_table **out, int32_t E, int32_t R, int32
     t->d_cand_cum = (const uint32_t *)(b + o_cum);
     t->d_rank_ptr = (const int32_t *)(b + o_rank);
     t->d_node_first_inst = (const int32_t *)(b + o_node);
+    t->d_inst_rank = (const int32_t *)(b + o_irank);
+    t->d_rank_node = (const int32_t *)(b + o_rnode);
     *out = t;
     return GRACE_OK;
 }
@@ -229,5 +235,7 @@ extern "C" size_t grace_workspace_bytes(int32_t T, int32_t E, int32_t k, int32_t
     need = std::max(need, 2 * grace::align_up(chunks_p * (size_t)I * 4, 256));
     need = std::max(need, grace::align_up(n * (size_t)f * el, 256));
     need = std::max(need, grace::align_up((size_t)T * (size_t)n_shared * (size_t)f * el, 256));
+    // send lists: five int32 arrays over the assignments + chunk histograms over up to GRACE_MAX_RANKS keys
+    need = std::max(need, 5 * grace::align_up(n * 4, 256) + 2 * grace::align_up(chunks_p * (size_t)GRACE_MAX_RANKS * 4, 256));
     return need + 256;
 }

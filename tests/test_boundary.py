@@ -75,6 +75,7 @@ def test_null_and_range_checks_without_device():
     assert lib.grace_combine(None, None, None, 1, 1, 8, 1, None, None, None) == -1               # null pointers
     assert lib.grace_combine(None, None, None, 0, 1, 8, 1, None, None, None) == 0                # nothing to do
     assert lib.grace_mfma_sustained(1, 1, None, None) == -1
+    assert lib.grace_send_lists(None, 0, None, 1, 1, None, None, None, None, None, None, None, None) == -1
 
 
 def test_workspace_bytes():

@@ -114,6 +114,28 @@ def test_route_wrr_policy_without_locality(name, local_rank):
     np.testing.assert_array_equal(host(g0.ti), host(g.ti))
 
 
+@pytest.mark.parametrize("name,T,local_rank", [("tiny", None, 0), ("tiny", 1, 2), ("olmoe", None, 0), ("qwen", 3001, 5),
+                                               ("dsv2lite", None, 0), ("dsv2lite", 5000, 13), ("mixtral", 2048, 6)])
+def test_send_lists_bit_exact(name, T, local_rank):
+    """De-duplicated per-rank / per-node send lists, expansion map and traffic counters."""
+    cfg = CONFIGS[name]
+    wl = make_workload(cfg, T=T)
+    pl = wl.placement
+    ref = oracle.route_permute(wl.logits, pl, cfg.k, local_rank)
+    sl = oracle.send_lists(ref.topk_inst, pl, local_rank, ref.order)
+    table = grace.GraceTable.from_placement(pl)
+    te, tw, ti, cnt = grace.grace_route(table, local_rank, dev(wl.logits), cfg.k)
+    rp, rt, np_, nt, ex, tr = grace.grace_send_lists(table, local_rank, ti)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(rp), sl.rank_send_ptr)
+    np.testing.assert_array_equal(host(rt)[:sl.rank_send_ptr[-1]], sl.rank_send_tok)
+    np.testing.assert_array_equal(host(np_), sl.node_send_ptr)
+    np.testing.assert_array_equal(host(nt)[:sl.node_send_ptr[-1]], sl.node_send_tok)
+    np.testing.assert_array_equal(host(ex), sl.expand)
+    np.testing.assert_array_equal(host(tr), sl.traffic)
+    assert (host(rt)[sl.rank_send_ptr[-1]:] == -1).all()      # nothing written past the lists
+
+
 @pytest.mark.parametrize("E,k,T", [(128, 8, 1500), (200, 5, 700), (256, 64, 300), (8, 8, 100), (3, 1, 129)])
 def test_route_wide_and_degenerate_expert_counts(E, k, T):
     """More than one expert per lane (E > 64), k = E, k = 1, ties everywhere."""

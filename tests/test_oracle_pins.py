@@ -123,6 +123,49 @@ def test_pick_and_permute_worked_example():
     assert ti_tar.reshape(-1).tolist() != c["topk_inst"]
 
 
+# ----------------------------------------------------- send lists (Section 5) --
+def test_send_lists_worked_examples():
+    g = gold("replica_pick_worked_example.json")
+    pl = table_from(g)
+    c = g["send_lists_rr0"]
+    sl = oracle.send_lists(np.array(g["case_rr0"]["topk_inst"], np.int32).reshape(6, 2), pl, 0)
+    assert sl.rank_send_ptr.tolist() == c["rank_send_ptr"] and sl.rank_send_tok.tolist() == c["rank_send_tok"]
+    assert sl.node_send_ptr.tolist() == c["node_send_ptr"] and sl.node_send_tok.tolist() == c["node_send_tok"]
+    c = g["send_lists_dup"]
+    sl = oracle.send_lists(np.array(c["topk_inst"], np.int32), pl, 0)
+    assert sl.rank_send_ptr.tolist() == c["rank_send_ptr"] and sl.rank_send_tok.tolist() == c["rank_send_tok"]
+    assert sl.node_send_ptr.tolist() == c["node_send_ptr"] and sl.node_send_tok.tolist() == c["node_send_tok"]
+    assert sl.expand.tolist() == c["expand"]
+    assert sl.traffic.tolist() == c["traffic"]
+
+
+@pytest.mark.parametrize("name,local_rank", [("olmoe", 0), ("dsv2lite", 13), ("qwen", 5)])
+def test_send_lists_against_library_unique(name, local_rank):
+    cfg = CONFIGS[name]
+    wl = make_workload(cfg, T=min(cfg.T, 1500))
+    pl = wl.placement
+    res = oracle.route_permute(wl.logits, pl, cfg.k, local_rank)
+    sl = oracle.send_lists(res.topk_inst, pl, local_rank, res.order)
+    T = res.topk_inst.shape[0]
+    ranks = res.order.g_rank[res.topk_inst]                  # [T, k]
+    nodes = pl.rank_node[ranks]
+    for r in range(pl.R):
+        want = np.unique(np.nonzero((ranks == r).any(1))[0])
+        np.testing.assert_array_equal(sl.rank_send_tok[sl.rank_send_ptr[r]:sl.rank_send_ptr[r + 1]], want)
+    for n in range(pl.N):
+        want = np.unique(np.nonzero((nodes == n).any(1))[0])
+        np.testing.assert_array_equal(sl.node_send_tok[sl.node_send_ptr[n]:sl.node_send_ptr[n + 1]], want)
+    # the expansion map leads every assignment back to its own token
+    flat_rank = ranks.reshape(-1)
+    tok = sl.rank_send_tok[sl.rank_send_ptr[flat_rank] + sl.expand]
+    np.testing.assert_array_equal(tok, np.repeat(np.arange(T), cfg.k))
+    # de-duplication never sends more than one row per assignment, and at least one per k assignments
+    my_node = pl.rank_node[local_rank]
+    assert sl.traffic[0] <= sl.traffic[1] <= cfg.k * max(sl.traffic[0], 1) or sl.traffic[1] == 0
+    assert sl.traffic[1] == int((nodes != my_node).sum())
+    assert sl.traffic[3] == int(((nodes == my_node) & (ranks != local_rank)).sum())
+
+
 # --------------------------------------------------------- O3 invariants --
 def _cands(pl, e, local_rank):
     ranks = pl.inst_rank[pl.inst_ptr[e]:pl.inst_ptr[e + 1]].tolist()
