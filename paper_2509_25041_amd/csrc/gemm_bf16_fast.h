@@ -4,8 +4,8 @@
 // wavefronts (2 along M x 4 along N, 128 x 64 outputs each, 32x32x16 MFMA).
 // Both operands are K-contiguous in HBM.  Tiles are copied HBM -> LDS with
 // direct-to-LDS 16-byte loads (no staging registers); the 16-byte chunk c of
-// tile row r is kept at chunk position c ^ (r & 7), which is applied on the
-// global address side because a direct load writes consecutive lanes to
+// tile row r is kept at chunk position c ^ ((r >> 1) & 7), which is applied on
+// the global address side because a direct load writes consecutive lanes to
 // consecutive LDS addresses.  Two LDS stages: the loads of step kt+1 are in
 // flight while step kt is multiplied; one barrier per step.
 //
@@ -19,8 +19,8 @@
 // is given a contiguous range of m-tiles and walks all n-tiles of an m-tile
 // consecutively, so the blocks resident on one XCD share activation rows and
 // (within a segment) weights in that XCD's L2.  Dealing groups of m-tiles
-// round-robin over the XCDs instead balances them better on paper but
-// measured 15-20 % slower on the Zipf-skewed workload.
+// round-robin over the XCDs instead balances them better on paper but was
+// not faster in interleaved repeated timings on the Zipf-skewed workload.
 #pragma once
 #include <type_traits>
 
@@ -75,14 +75,7 @@ __device__ __forceinline__ void wait_vmcnt() {
     else static_assert(N == 0, "unsupported vmcnt");
 }
 
-#ifdef GRACE_GEMM_TRACE
-__device__ long long g_trace[4 * 4096];
-#define GRACE_TRACE(slot) do { if (threadIdx.x == 0 && blockIdx.x < 4096) g_trace[blockIdx.x * 4 + (slot)] = wall_clock64(); } while (0)
-#else
-#define GRACE_TRACE(slot) do { } while (0)
-#endif
-
-template <bool FUSED_UP, typename G, int DEBUG = 0>
+template <bool FUSED_UP, typename G>
 __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_fast_kernel(const GemmArgs g, int n_tiles_n) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     constexpr int BK = G::BK, NSTAGE = G::NSTAGE, LOADS = G::LOADS;
@@ -91,7 +84,6 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_fast_kernel(const GemmAr
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar
     const int wm = wave >> 2, wn = wave & 3;
 
-    GRACE_TRACE(0);
     // ---- tile of this block -------------------------------------------------
     // XCD x owns the contiguous m-tile range [x * per_xcd, (x + 1) * per_xcd) and walks it in
     // (m-tile, n-tile) order, so the 32 blocks resident on an XCD cover a few consecutive
@@ -195,7 +187,6 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_fast_kernel(const GemmAr
     };
     wait_younger(min(NSTAGE - 1, nk - 1));  // stages 1 .. NSTAGE-1 may still be in flight
     asm volatile("s_barrier" ::: "memory");
-    GRACE_TRACE(1);
 
     int stage_c = 0;
     if (n_valid == 4) {
@@ -224,37 +215,35 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_fast_kernel(const GemmAr
                         wait_younger(min(NSTAGE - 2, nk - 2 - kt));  // in flight: stages kt+2 .. kt+NSTAGE-1
                         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                         asm volatile("s_barrier" ::: "memory");
-                        if (HAS_LOADS && DEBUG != 1) issue_loads();
-                        if (DEBUG != 2) fetch(nxt, st_next, 0);
+                        if (HAS_LOADS) issue_loads();
+                        fetch(nxt, st_next, 0);
                     }
                 } else {
-                    if (DEBUG != 2) fetch(nxt, st, ks + 1);
+                    fetch(nxt, st, ks + 1);
                 }
-                if (DEBUG != 2) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < 4; ++i)
 #pragma unroll
-                        for (int jj = 0; jj < 2; ++jj)
-                            acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][jj], fa[cur][i], acc[i][jj], 0, 0, 0);
-                    // issue order inside a group: the 6 fragment reads of the next group (and, after the
-                    // barrier, the 2 * LOADS direct-to-LDS loads) are spread between the 8 MFMAs
-                    if (last && HAS_NEXT && HAS_LOADS && DEBUG != 1) {
+                    for (int jj = 0; jj < 2; ++jj)
+                        acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][jj], fa[cur][i], acc[i][jj], 0, 0, 0);
+                // issue order inside a group: the 6 fragment reads of the next group (and, after the
+                // barrier, the 2 * LOADS direct-to-LDS loads) are spread between the 8 MFMAs
+                if (last && HAS_NEXT && HAS_LOADS) {
 #pragma unroll
-                        for (int r = 0; r < 8; ++r) {
-                            if (r < 2 * LOADS) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // 1 VMEM
-                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                      // 1 MFMA
-                            if (r < 6) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);           // 1 LDS read
-                        }
-                    } else if (!last || HAS_NEXT) {
-#pragma unroll
-                        for (int r = 0; r < 6; ++r) {
-                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
-                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 LDS read
-                        }
-                        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                    for (int r = 0; r < 8; ++r) {
+                        if (r < 2 * LOADS) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // 1 VMEM
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                      // 1 MFMA
+                        if (r < 6) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);           // 1 LDS read
                     }
-                    __builtin_amdgcn_sched_barrier(0);
+                } else if (!last || HAS_NEXT) {
+#pragma unroll
+                    for (int r = 0; r < 6; ++r) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 LDS read
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
         };
         using T_ = std::integral_constant<bool, true>;
@@ -293,7 +282,6 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_fast_kernel(const GemmAr
         }
     }
 
-    GRACE_TRACE(2);
     // ---- epilogue -------------------------------------------------------------------
     // The weight fragment is the MFMA's first operand, so acc[i][jj] holds a transposed 32x32
     // tile: element v of lane l is (n = 8*(v/4) + 4*(l/32) + v%4, m = l%32), i.e. four
@@ -352,7 +340,6 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_fast_kernel(const GemmAr
             }
         }
     }
-    GRACE_TRACE(3);
 }
 
 // Grid size for `m_bound` rows in at most `n_seg` segments.
