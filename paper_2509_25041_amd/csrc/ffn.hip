@@ -7,31 +7,54 @@
 //   down: y[p, m]  = sum_n h[p,n] Wd[m,n]                                     K = f, N = d
 // Rows are grouped by instance: the rows of one rank are a contiguous range of
 // the dispatch buffer, subdivided per local slot by inst_off (read on the
-// device; there is no host synchronisation).  The grid is sized from an upper
-// bound of the tile count and surplus blocks exit at once.
+// device; there is no host synchronisation).  The bf16 kernel is persistent (one
+// workgroup per compute unit walks the tiles); the fallback kernels size their
+// grid from an upper bound of the tile count and surplus blocks exit at once.
 #include "bf16.h"
 #include "common.h"
-#include "gemm_bf16_fast.h"
 #include "gemm_bf16_generic.h"
+#include "gemm_bf16_persist.h"
 #include "gemm_common.h"
 #include "gemm_f32.h"
 
 namespace grace {
 
+// Compute units of the current device (cached per device).
+static int compute_units() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return -1;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
 template <bool FUSED_UP>
 static int launch_gemm(const GemmArgs &g, grace_dtype dt, int64_t m_bound, hipStream_t st, const char *what) {
     if (m_bound <= 0 || g.N <= 0 || g.K <= 0) return GRACE_OK;
-    if (dt == GRACE_BF16 && g.K % fast::DefaultGeo::BK == 0 && g.kseg_len % fast::DefaultGeo::BK == 0) {
-        // large-tile kernel: needs 128 KB of dynamic LDS, opted into once per process
-        static const hipError_t attr = hipFuncSetAttribute((const void *)fast::gemm_bf16_fast_kernel<FUSED_UP, fast::DefaultGeo>,
-                                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                           fast::DefaultGeo::LDS_BYTES);
-        if (attr != hipSuccess) return fail(GRACE_EHIP, "%s: cannot reserve LDS: %s", what, hipGetErrorString(attr));
-        constexpr int BN = FUSED_UP ? 128 : 256;
-        const int ntn = (g.N + BN - 1) / BN;
-        const int64_t grid = fast::grid_blocks(m_bound, g.seg_off ? g.S : 1, ntn);
-        if (grid > INT32_MAX) return fail(GRACE_ESHAPE, "%s: grid too large", what);
-        fast::gemm_bf16_fast_kernel<FUSED_UP, fast::DefaultGeo><<<(unsigned)grid, fast::THREADS, fast::DefaultGeo::LDS_BYTES, st>>>(g, ntn);
+    const int n_seg = g.seg_off ? g.S : 1;
+    if (dt == GRACE_BF16 && g.K % pers::BK == 0 && g.kseg_len % pers::BK == 0 && g.K >= 2 * pers::BK &&
+        n_seg <= pers::MAX_SEGMENTS) {
+        // persistent large-tile kernel: one workgroup per compute unit, up to 160 KB of dynamic LDS
+        const int n_cu = compute_units();
+        if (n_cu <= 0) return fail(GRACE_EHIP, "%s: cannot query the device", what);
+        using SH = pers::Shape<FUSED_UP>;
+        const int ntn = (g.N + SH::BN - 1) / SH::BN;
+        const int grid = pers::grid_blocks(n_cu);
+        if (n_seg <= 64) {
+            static const hipError_t attr = hipFuncSetAttribute((const void *)pers::gemm_bf16_persist_kernel<FUSED_UP, 1>,
+                                                               hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
+            if (attr != hipSuccess) return fail(GRACE_EHIP, "%s: cannot reserve LDS: %s", what, hipGetErrorString(attr));
+            pers::gemm_bf16_persist_kernel<FUSED_UP, 1><<<grid, pers::THREADS, SH::LDS_BYTES, st>>>(g, ntn);
+        } else {
+            static const hipError_t attr = hipFuncSetAttribute((const void *)pers::gemm_bf16_persist_kernel<FUSED_UP, 4>,
+                                                               hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
+            if (attr != hipSuccess) return fail(GRACE_EHIP, "%s: cannot reserve LDS: %s", what, hipGetErrorString(attr));
+            pers::gemm_bf16_persist_kernel<FUSED_UP, 4><<<grid, pers::THREADS, SH::LDS_BYTES, st>>>(g, ntn);
+        }
     } else if (dt == GRACE_BF16) {
         constexpr int BN = FUSED_UP ? 64 : 128;
         const int64_t mt = m_bound / BM + (g.seg_off ? g.S : 1);

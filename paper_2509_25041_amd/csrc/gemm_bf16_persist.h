@@ -1,0 +1,395 @@
+// bf16 MFMA grouped GEMM for gfx950: persistent workgroups, large tiles.
+//
+// One workgroup per compute unit walks a list of output tiles.  Tile = 256
+// activation rows x 256 weight rows, K in steps of 64, 8 wavefronts (2 along M
+// x 4 along N, 128 x 64 outputs each, 32x32x16 MFMA).  Both operands are
+// K-contiguous in HBM and are copied HBM -> LDS with direct-to-LDS 16-byte
+// loads (no staging registers); the 16-byte chunk c of tile row r is kept at
+// chunk position c ^ ((r >> 1) & 7) (conflict-free fragment reads), applied on
+// the global address side because a direct load writes consecutive lanes to
+// consecutive LDS addresses.
+//
+// The K loop is flattened over the workgroup's tiles: two LDS stages, and the
+// loads issued in step g always belong to step g + 2, whether that is in the
+// same tile or the next one.  So the operand pipeline never drains between
+// tiles: the first two steps of the next tile are in flight while the current
+// tile's accumulators are converted and written out, and those writes drain
+// while the next tile is being multiplied.  The epilogue stages through a
+// small LDS region private to each wavefront (separate from the operand
+// stages), so it needs no workgroup barrier.
+//
+// Ragged row segments (one per local expert slot): rows past the end of a
+// segment are clamped to its last row when loading and never stored; a
+// wavefront whose 128 rows all lie past the end skips its MFMAs.  Weight rows
+// past N are clamped likewise.  Every wavefront keeps the segment table in
+// registers (1 or 4 segments per lane, so at most 256 segments) and finds a
+// tile's segment with a ballot; there is no tile table in memory.
+// Preconditions (checked by the launcher): K and the K segment length are
+// multiples of 64, K >= 128, at most 256 segments, grid a multiple of 8.
+//
+// Tile order is XCD-aware: workgroups are dealt round-robin to the 8 XCDs, so
+// block b runs on XCD b % 8 (checked with HW_REG_XCC_ID).  Each XCD owns a
+// contiguous range of m-tiles and its workgroups take consecutive (m-tile,
+// n-tile) pairs, so at any time an XCD works on a few m-tiles x all n-tiles
+// and shares their operands in its own L2.
+#pragma once
+#include <type_traits>
+
+#include "bf16.h"
+#include "gemm_common.h"
+
+namespace grace {
+namespace pers {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef const __attribute__((address_space(1))) void global_void_t;
+
+constexpr int BM = 256, BROWS = 256, THREADS = 512, N_XCD = 8;
+constexpr int BK = 64, NSTAGE = 2, KS = BK / 16;
+constexpr int ROW_BYTES = BK * 2;              // one tile row in LDS
+constexpr int CPR = BK / 8;                    // 16-byte chunks per row
+constexpr int ROWS_PER_LOAD = 1024 / ROW_BYTES;  // rows covered by one wavefront-wide 16-byte load
+constexpr int LOADS = BM / (8 * ROWS_PER_LOAD);  // loads per lane per operand per stage
+constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BROWS * ROW_BYTES, STAGE_BYTES = A_BYTES + B_BYTES;
+constexpr int MAX_SEG_PER_LANE = 4, MAX_SEGMENTS = 64 * MAX_SEG_PER_LANE;
+
+template <bool FUSED_UP>
+struct Shape {
+    static constexpr int BN = FUSED_UP ? 128 : 256;   // output columns per tile
+    static constexpr int BNW = FUSED_UP ? 32 : 64;    // output columns per wavefront
+    static constexpr int ROWB = BNW * 2;              // bytes per staged output row
+    static constexpr int STG_WAVE = 32 * ROWB;        // staging per wavefront: one 32-row sub-tile
+    static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES + 8 * STG_WAVE;
+};
+
+__device__ __forceinline__ int swizzle_key(int row) { return (row >> 1) & (CPR - 1); }
+
+__device__ __forceinline__ void load16_to_lds(const void *gptr, char *lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((global_void_t *)gptr, (lds_void_t *)lds_wave_base, 16, 0, 0);
+}
+
+struct Tile {
+    int slot, m0, m_end;  // segment, first row, end of the segment
+};
+
+// SEG_PER_LANE: 1 for up to 64 row segments, 4 for up to 256.
+template <bool FUSED_UP, int SEG_PER_LANE>
+__global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const GemmArgs g, int n_tiles_n) {
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    using SH = Shape<FUSED_UP>;
+    constexpr int BN = SH::BN;
+    const int tid = (int)threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar
+    const int wm = wave >> 2, wn = wave & 3;
+
+    // ---- segment table in registers: lane l holds segments SEG_PER_LANE * l .. + SEG_PER_LANE - 1 ----
+    int seg_lo[SEG_PER_LANE], seg_hi[SEG_PER_LANE], seg_base[SEG_PER_LANE];
+    int total_mt;
+    {
+        int lane_tiles = 0;
+#pragma unroll
+        for (int q = 0; q < SEG_PER_LANE; ++q) {
+            const int s = lane * SEG_PER_LANE + q;
+            int lo = 0, hi = 0;
+            if (g.seg_off) {
+                if (s < g.S) { lo = g.seg_off[s]; hi = max(lo, g.seg_off[s + 1]); }
+            } else if (s == 0) {
+                hi = g.M_single;
+            }
+            seg_lo[q] = lo;
+            seg_hi[q] = hi;
+            seg_base[q] = lane_tiles;                 // made global below
+            lane_tiles += (hi - lo + BM - 1) / BM;    // hi >= lo
+        }
+        int incl = lane_tiles;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += up;
+        }
+        const int lane_base = incl - lane_tiles;
+#pragma unroll
+        for (int q = 0; q < SEG_PER_LANE; ++q) seg_base[q] += lane_base;
+        total_mt = __builtin_amdgcn_readlane(incl, 63);
+    }
+    // (slot, first row, segment end) of m-tile mt < total_mt, as scalars
+    auto lookup = [&](int mt) {
+        int slot = 0, m0 = 0, m_end = 0;
+        bool hit = false;
+#pragma unroll
+        for (int q = 0; q < SEG_PER_LANE; ++q) {
+            const int rel = mt - seg_base[q];
+            const int tiles = (seg_hi[q] - seg_lo[q] + BM - 1) / BM;
+            if (rel >= 0 && rel < tiles) {
+                hit = true;
+                slot = lane * SEG_PER_LANE + q;
+                m0 = seg_lo[q] + rel * BM;
+                m_end = seg_hi[q];
+            }
+        }
+        const unsigned long long owners = __ballot(hit);
+        const int src = owners ? __builtin_ctzll(owners) : 0;
+        Tile t;
+        t.slot = __builtin_amdgcn_readlane(slot, src);
+        t.m0 = __builtin_amdgcn_readlane(m0, src);
+        t.m_end = __builtin_amdgcn_readlane(m_end, src);
+        return t;
+    };
+
+    // ---- this workgroup's tiles ------------------------------------------------------------
+    const int nblk = (int)gridDim.x / N_XCD;                          // workgroups per XCD
+    const int xcd = (int)blockIdx.x % N_XCD, bslot = (int)blockIdx.x / N_XCD;
+    const int mt_each = total_mt / N_XCD, mt_rem = total_mt % N_XCD;  // first mt_rem XCDs take one more
+    const int mt_first = xcd * mt_each + min(xcd, mt_rem);
+    const int njobs = (mt_each + (xcd < mt_rem ? 1 : 0)) * n_tiles_n;
+    int job = bslot;
+    if (job >= njobs) return;
+
+    const uint16_t *A = (const uint16_t *)g.A;
+    const int nk = g.K / BK;
+
+    // ---- this lane's load sources (fixed rows of the current load tile, advancing along K) ----
+    // One wavefront-wide load fills 1 KB of LDS = ROWS_PER_LOAD consecutive tile rows; lane l
+    // lands at row l / CPR, chunk position l % CPR.
+    const int lrow = lane / CPR, lpos = lane % CPR;
+    const uint16_t *a_src[LOADS], *b_src[LOADS];
+    int64_t kb = 0;
+    int kpos = 0, k_issue = 0, stage_issue = 0;
+    auto set_sources = [&](const Tile &t, int n0) {
+        const uint16_t *B0 = (const uint16_t *)g.B0 + (int64_t)t.slot * g.b_slot_stride;
+        const uint16_t *B1 = FUSED_UP ? (const uint16_t *)g.B1 + (int64_t)t.slot * g.b_slot_stride : nullptr;
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int tr = (i * 8 + wave) * ROWS_PER_LOAD + lrow;  // tile row
+            const int gchunk = lpos ^ swizzle_key(tr);               // global chunk that lands at position lpos
+            const int m = min(t.m0 + tr, t.m_end - 1);
+            a_src[i] = A + (int64_t)m * g.lda + gchunk * 8;
+            int n;
+            const uint16_t *Bm;
+            if (FUSED_UP) { n = n0 + (tr & 127); Bm = (tr >> 7) ? B1 : B0; }
+            else { n = n0 + tr; Bm = B0; }
+            n = min(n, g.N - 1);
+            b_src[i] = Bm + (int64_t)n * g.ldb + gchunk * 8;
+        }
+        kb = 0;
+        kpos = 0;
+        k_issue = 0;
+    };
+    // weight K offset of the step being loaded jumps at K segment ends (a step never straddles one)
+    auto issue_loads = [&]() {
+        char *sa = smem + stage_issue * STAGE_BYTES + wave * 1024;
+        char *sb = sa + A_BYTES;
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            load16_to_lds(a_src[i] + k_issue, sa + i * 8192);
+            load16_to_lds(b_src[i] + kb, sb + i * 8192);
+        }
+        k_issue += BK;
+        kb += BK;
+        kpos += BK;
+        if (kpos == g.kseg_len) { kpos = 0; kb += g.kseg_stride - g.kseg_len; }
+        stage_issue ^= 1;
+    };
+
+    // fragment addresses: row r = base + (lane & 31), chunk c = 2*ks + (lane >> 5) stored at c ^ key(r)
+    const int frow = lane & 31, fhalf = lane >> 5, fkey = swizzle_key(frow);  // bases are multiples of 32
+    int a_off[4], b_off[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a_off[i] = (wm * 128 + i * 32 + frow) * ROW_BYTES;
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+        b_off[jj] = A_BYTES + ((FUSED_UP ? jj * 128 + wn * 32 : wn * 64 + jj * 32) + frow) * ROW_BYTES;
+    int pc[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) pc[ks] = ((ks * 2 + fhalf) ^ fkey) * 16;
+
+    bf16x8_t fa[2][4], fb[2][2];
+    auto fetch = [&](int buf, const char *st, int ks) {
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) fb[buf][jj] = *(const bf16x8_t *)(st + b_off[jj] + pc[ks]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fa[buf][i] = *(const bf16x8_t *)(st + a_off[i] + pc[ks]);
+    };
+
+    // ---- one K step ---------------------------------------------------------------------------
+    // Before the MFMAs of its last 16-wide K group the workgroup synchronises once: by then every
+    // wavefront has read all of this step's stage (fragments are fetched one group ahead), so the
+    // buffer is handed to the loads of step g + 2; and each wavefront has waited for its own loads
+    // of step g + 1, so after the barrier that stage has landed.  CROSS: fetch the first fragments
+    // of the next step under the last MFMAs (not across a tile boundary).
+    int stage_c = 0;
+    auto step = [&](f32x16_t (&acc)[4][2], auto load_mode, auto cross, bool load_now) {
+        // load_mode 1: always issue the loads (interleaved with the MFMAs); 2: only if load_now
+        constexpr int LOAD_MODE = decltype(load_mode)::value;
+        constexpr bool HAS_LOADS = LOAD_MODE == 1, CROSS = decltype(cross)::value;
+        const char *st = smem + stage_c * STAGE_BYTES;
+        stage_c ^= 1;
+        const char *st_next = smem + stage_c * STAGE_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;  // KS is even: parity restarts every step
+            const bool last = ks == KS - 1;
+            if (last) {
+                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                asm volatile("s_barrier" ::: "memory");
+                if (HAS_LOADS) issue_loads();
+                if (LOAD_MODE == 2 && load_now) issue_loads();
+                if (CROSS) fetch(nxt, st_next, 0);
+            } else {
+                fetch(nxt, st, ks + 1);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+                    acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][jj], fa[cur][i], acc[i][jj], 0, 0, 0);
+            // issue order inside a group: the 6 fragment reads of the next group (and, after the
+            // barrier, the 2 * LOADS direct-to-LDS loads) are spread between the 8 MFMAs
+            if (last && HAS_LOADS && CROSS) {
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    if (r < 2 * LOADS) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // 1 VMEM
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                      // 1 MFMA
+                    if (r < 6) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);           // 1 LDS read
+                }
+            } else if (last && HAS_LOADS) {
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    if (r < 2 * LOADS) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                }
+            } else if (!last || CROSS) {
+#pragma unroll
+                for (int r = 0; r < 6; ++r) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 LDS read
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // the same step for a wavefront with no valid rows in this tile: synchronise and load only
+    auto idle_step = [&](bool has_loads) {
+        stage_c ^= 1;
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        asm volatile("s_barrier" ::: "memory");
+        if (has_loads) issue_loads();
+    };
+    using T_ = std::integral_constant<bool, true>;
+    using F_ = std::integral_constant<bool, false>;
+    using ALWAYS_ = std::integral_constant<int, 1>;
+    using MAYBE_ = std::integral_constant<int, 2>;
+
+    // ---- epilogue ---------------------------------------------------------------------------------
+    // The weight fragment is the MFMA's first operand, so acc[i][jj] holds a transposed 32x32 tile:
+    // element v of lane l is (n = 8*(v/4) + 4*(l/32) + v%4, m = l%32), i.e. four consecutive output
+    // columns of one row per group of four values.  Per 32-row sub-tile the wavefront packs to
+    // bf16, transposes through its own LDS region (16-byte chunks XOR-swizzled by row) and writes
+    // whole rows with 16-byte stores.
+    constexpr int BNW = SH::BNW, ROWB = SH::ROWB;
+    constexpr int CH = ROWB / 16;               // 16-byte chunks per staged row
+    constexpr int KSH = (ROWB == 128) ? 1 : 2;  // rows per 256 bytes of LDS = 1 << KSH
+    char *stg = smem + NSTAGE * STAGE_BYTES + wave * SH::STG_WAVE;
+    const int fhalf8 = fhalf * 8;
+    auto epilogue = [&](f32x16_t (&acc)[4][2], const Tile &t, int n0, int n_valid) {
+        uint16_t *out = (uint16_t *)g.out;
+        constexpr int ROWS_PER_IT = 64 / CH;
+        const int rr = lane / CH, cc = lane % CH;
+        const int ncol = n0 + wn * BNW + cc * 8;
+        const int wkey = (frow >> KSH) & (CH - 1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (i >= n_valid) break;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (FUSED_UP) {
+                    float h[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float gt = acc[i][0][q * 4 + r], up = acc[i][1][q * 4 + r];
+                        h[r] = gt * __frcp_rn(1.0f + __expf(-gt)) * up;
+                    }
+                    uint2 pk = make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
+                    *(uint2 *)(stg + frow * ROWB + ((q ^ wkey) * 16) + fhalf8) = pk;
+                } else {
+#pragma unroll
+                    for (int jj = 0; jj < 2; ++jj) {
+                        uint2 pk = make_uint2(pack_bf16x2(acc[i][jj][q * 4 + 0], acc[i][jj][q * 4 + 1]),
+                                              pack_bf16x2(acc[i][jj][q * 4 + 2], acc[i][jj][q * 4 + 3]));
+                        *(uint2 *)(stg + frow * ROWB + (((jj * 4 + q) ^ wkey) * 16) + fhalf8) = pk;
+                    }
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wavefront's own writes, read back below
+#pragma unroll
+            for (int it = 0; it < 32 / ROWS_PER_IT; ++it) {
+                const int ml = it * ROWS_PER_IT + rr;
+                const int row = t.m0 + wm * 128 + i * 32 + ml;
+                const int key = (ml >> KSH) & (CH - 1);
+                const uint4 v = *(const uint4 *)(stg + ml * ROWB + ((cc ^ key) * 16));
+                if (row < t.m_end && ncol < g.N) *(uint4 *)(out + (int64_t)row * g.ldo + ncol) = v;
+            }
+            // LDS operations of one wavefront execute in order: the next sub-tile's writes cannot
+            // overtake these reads
+        }
+    };
+
+    // ---- tile loop ----------------------------------------------------------------------------------
+    Tile cur = lookup(mt_first + job / n_tiles_n);
+    int cur_n0 = (job % n_tiles_n) * BN;
+    set_sources(cur, cur_n0);
+    issue_loads();
+    issue_loads();  // nk >= 2
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");  // step 0 landed; the 2 * LOADS loads of step 1 may be in flight
+    static_assert(2 * LOADS == 8, "prologue wait assumes 8 loads per stage and lane");
+    asm volatile("s_barrier" ::: "memory");
+    for (;;) {
+        const int next_job = job + nblk;
+        const bool has_next = next_job < njobs;  // uniform
+        Tile nxt = cur;
+        int nxt_n0 = cur_n0;
+        if (has_next) {
+            nxt = lookup(mt_first + next_job / n_tiles_n);
+            nxt_n0 = (next_job % n_tiles_n) * BN;
+        }
+        // 32-row sub-tiles of this wavefront that hold at least one valid row (scalar)
+        const int n_valid = max(0, min(4, (cur.m_end - (cur.m0 + wm * 128) + 31) / 32));
+        if (n_valid > 0) {
+            f32x16_t acc[4][2];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[i][jj][v] = 0.0f;
+            fetch(0, smem + stage_c * STAGE_BYTES, 0);
+            for (int kt = 0; kt + 2 < nk; ++kt) step(acc, ALWAYS_{}, T_{}, true);
+            // the last two steps load the first two steps of the next tile, if there is one
+            if (has_next) set_sources(nxt, nxt_n0);
+            step(acc, MAYBE_{}, T_{}, has_next);
+            step(acc, MAYBE_{}, F_{}, has_next);
+            epilogue(acc, cur, cur_n0, n_valid);
+        } else {
+            for (int kt = 0; kt + 2 < nk; ++kt) idle_step(true);
+            if (has_next) set_sources(nxt, nxt_n0);
+            idle_step(has_next);
+            idle_step(has_next);
+        }
+        if (!has_next) break;
+        cur = nxt;
+        cur_n0 = nxt_n0;
+        job = next_job;
+    }
+}
+
+// Workgroups to launch on a device with `n_cu` compute units: one per compute unit, a multiple of 8.
+inline int grid_blocks(int n_cu) {
+    const int g = n_cu / N_XCD * N_XCD;
+    return g < N_XCD ? N_XCD : g;
+}
+
+}  // namespace pers
+}  // namespace grace
