@@ -36,9 +36,9 @@ template <bool FUSED_UP>
 static int launch_gemm(const GemmArgs &g, grace_dtype dt, int64_t m_bound, hipStream_t st, const char *what) {
     if (m_bound <= 0 || g.N <= 0 || g.K <= 0) return GRACE_OK;
     const int n_seg = g.seg_off ? g.S : 1;
-    if (dt == GRACE_BF16 && g.K % pers::BK == 0 && g.kseg_len % pers::BK == 0 && g.K >= 2 * pers::BK &&
+    if (dt == GRACE_BF16 && g.K % pers::BK == 0 && g.kseg_len % pers::BK == 0 && g.K >= pers::MIN_K_STEPS * pers::BK &&
         n_seg <= pers::MAX_SEGMENTS) {
-        // persistent large-tile kernel: one workgroup per compute unit, up to 160 KB of dynamic LDS
+        // persistent large-tile kernel: one workgroup per compute unit, 160 KB of dynamic LDS
         const int n_cu = compute_units();
         if (n_cu <= 0) return fail(GRACE_EHIP, "%s: cannot query the device", what);
         using SH = pers::Shape<FUSED_UP>;
@@ -46,14 +46,14 @@ static int launch_gemm(const GemmArgs &g, grace_dtype dt, int64_t m_bound, hipSt
         const int grid = pers::grid_blocks(n_cu);
         if (n_seg <= 64) {
             static const hipError_t attr = hipFuncSetAttribute((const void *)pers::gemm_bf16_persist_kernel<FUSED_UP, 1>,
-                                                               hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
+                                                               hipFuncAttributeMaxDynamicSharedMemorySize, pers::LDS_BYTES);
             if (attr != hipSuccess) return fail(GRACE_EHIP, "%s: cannot reserve LDS: %s", what, hipGetErrorString(attr));
-            pers::gemm_bf16_persist_kernel<FUSED_UP, 1><<<grid, pers::THREADS, SH::LDS_BYTES, st>>>(g, ntn);
+            pers::gemm_bf16_persist_kernel<FUSED_UP, 1><<<grid, pers::THREADS, pers::LDS_BYTES, st>>>(g, ntn);
         } else {
             static const hipError_t attr = hipFuncSetAttribute((const void *)pers::gemm_bf16_persist_kernel<FUSED_UP, 4>,
-                                                               hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
+                                                               hipFuncAttributeMaxDynamicSharedMemorySize, pers::LDS_BYTES);
             if (attr != hipSuccess) return fail(GRACE_EHIP, "%s: cannot reserve LDS: %s", what, hipGetErrorString(attr));
-            pers::gemm_bf16_persist_kernel<FUSED_UP, 4><<<grid, pers::THREADS, SH::LDS_BYTES, st>>>(g, ntn);
+            pers::gemm_bf16_persist_kernel<FUSED_UP, 4><<<grid, pers::THREADS, pers::LDS_BYTES, st>>>(g, ntn);
         }
     } else if (dt == GRACE_BF16) {
         constexpr int BN = FUSED_UP ? 64 : 128;

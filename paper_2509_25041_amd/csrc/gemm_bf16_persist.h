@@ -9,14 +9,19 @@
 // the global address side because a direct load writes consecutive lanes to
 // consecutive LDS addresses.
 //
-// The K loop is flattened over the workgroup's tiles: two LDS stages, and the
-// loads issued in step g always belong to step g + 2, whether that is in the
-// same tile or the next one.  So the operand pipeline never drains between
-// tiles: the first two steps of the next tile are in flight while the current
-// tile's accumulators are converted and written out, and those writes drain
-// while the next tile is being multiplied.  The epilogue stages through a
-// small LDS region private to each wavefront (separate from the operand
-// stages), so it needs no workgroup barrier.
+// All 160 KB of LDS hold operand buffers: two for the activation tile and
+// three for the weight tile (32 KB each).  The K loop is flattened over the
+// workgroup's tiles: in step g, once every wavefront has read the buffers of
+// step g, the activation loads of step g + 2 and the weight loads of step
+// g + 3 are issued, whether those steps are in the same tile or the next one.
+// A batch of loads needs longer than one step to land, which a plain double
+// buffer cannot hide; with this split the activation batch is half as large
+// and the weight batch has two steps.  The pipeline never drains between
+// tiles: the first steps of the next tile are in flight while the current
+// tile's accumulators are converted and written out.  The epilogue stages
+// through the weight buffer that was consumed last (each wavefront uses
+// exactly the bytes its own next weight loads will overwrite, and issues those
+// loads after it is done), so it needs no workgroup barrier.
 //
 // Ragged row segments (one per local expert slot): rows past the end of a
 // segment are clamped to its last row when loading and never stored; a
@@ -25,7 +30,7 @@
 // registers (1 or 4 segments per lane, so at most 256 segments) and finds a
 // tile's segment with a ballot; there is no tile table in memory.
 // Preconditions (checked by the launcher): K and the K segment length are
-// multiples of 64, K >= 128, at most 256 segments, grid a multiple of 8.
+// multiples of 64, K >= 192, at most 256 segments, grid a multiple of 8.
 //
 // Tile order is XCD-aware: workgroups are dealt round-robin to the 8 XCDs, so
 // block b runs on XCD b % 8 (checked with HW_REG_XCC_ID).  Each XCD owns a
@@ -47,12 +52,16 @@ typedef __attribute__((address_space(3))) void lds_void_t;
 typedef const __attribute__((address_space(1))) void global_void_t;
 
 constexpr int BM = 256, BROWS = 256, THREADS = 512, N_XCD = 8;
-constexpr int BK = 64, NSTAGE = 2, KS = BK / 16;
+constexpr int BK = 64, KS = BK / 16;
+constexpr int NBUF_A = 2, NBUF_B = 3;          // LDS buffers per operand
+constexpr int MIN_K_STEPS = 3;
 constexpr int ROW_BYTES = BK * 2;              // one tile row in LDS
 constexpr int CPR = BK / 8;                    // 16-byte chunks per row
 constexpr int ROWS_PER_LOAD = 1024 / ROW_BYTES;  // rows covered by one wavefront-wide 16-byte load
 constexpr int LOADS = BM / (8 * ROWS_PER_LOAD);  // loads per lane per operand per stage
-constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BROWS * ROW_BYTES, STAGE_BYTES = A_BYTES + B_BYTES;
+constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BROWS * ROW_BYTES;
+constexpr int B_BASE = NBUF_A * A_BYTES;       // weight buffers follow the activation buffers
+constexpr int LDS_BYTES = NBUF_A * A_BYTES + NBUF_B * B_BYTES;
 constexpr int MAX_SEG_PER_LANE = 4, MAX_SEGMENTS = 64 * MAX_SEG_PER_LANE;
 
 template <bool FUSED_UP>
@@ -60,9 +69,8 @@ struct Shape {
     static constexpr int BN = FUSED_UP ? 128 : 256;   // output columns per tile
     static constexpr int BNW = FUSED_UP ? 32 : 64;    // output columns per wavefront
     static constexpr int ROWB = BNW * 2;              // bytes per staged output row
-    static constexpr int STG_WAVE = 32 * ROWB;        // staging per wavefront: one 32-row sub-tile
-    static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES + 8 * STG_WAVE;
 };
+static_assert(LOADS == 4 && 32 * 128 <= LOADS * 1024, "a wavefront's share of a weight buffer must hold one staged 32-row sub-tile");
 
 __device__ __forceinline__ int swizzle_key(int row) { return (row >> 1) & (CPR - 1); }
 
@@ -156,16 +164,25 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     const int lrow = lane / CPR, lpos = lane % CPR;
     const uint16_t *a_src[LOADS], *b_src[LOADS];
     int64_t kb = 0;
-    int kpos = 0, k_issue = 0, stage_issue = 0;
-    auto set_sources = [&](const Tile &t, int n0) {
-        const uint16_t *B0 = (const uint16_t *)g.B0 + (int64_t)t.slot * g.b_slot_stride;
-        const uint16_t *B1 = FUSED_UP ? (const uint16_t *)g.B1 + (int64_t)t.slot * g.b_slot_stride : nullptr;
+    int kpos = 0, ka = 0;
+    int a_iss = 0, b_iss = 0;  // buffers the next loads go to
+    auto set_a_sources = [&](const Tile &t) {
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
             const int tr = (i * 8 + wave) * ROWS_PER_LOAD + lrow;  // tile row
             const int gchunk = lpos ^ swizzle_key(tr);               // global chunk that lands at position lpos
             const int m = min(t.m0 + tr, t.m_end - 1);
             a_src[i] = A + (int64_t)m * g.lda + gchunk * 8;
+        }
+        ka = 0;
+    };
+    auto set_b_sources = [&](const Tile &t, int n0) {
+        const uint16_t *B0 = (const uint16_t *)g.B0 + (int64_t)t.slot * g.b_slot_stride;
+        const uint16_t *B1 = FUSED_UP ? (const uint16_t *)g.B1 + (int64_t)t.slot * g.b_slot_stride : nullptr;
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int tr = (i * 8 + wave) * ROWS_PER_LOAD + lrow;
+            const int gchunk = lpos ^ swizzle_key(tr);
             int n;
             const uint16_t *Bm;
             if (FUSED_UP) { n = n0 + (tr & 127); Bm = (tr >> 7) ? B1 : B0; }
@@ -175,22 +192,29 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
         }
         kb = 0;
         kpos = 0;
-        k_issue = 0;
     };
-    // weight K offset of the step being loaded jumps at K segment ends (a step never straddles one)
-    auto issue_loads = [&]() {
-        char *sa = smem + stage_issue * STAGE_BYTES + wave * 1024;
-        char *sb = sa + A_BYTES;
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            load16_to_lds(a_src[i] + k_issue, sa + i * 8192);
-            load16_to_lds(b_src[i] + kb, sb + i * 8192);
-        }
-        k_issue += BK;
+    auto issue_a_one = [&](int i) { load16_to_lds(a_src[i] + ka, smem + a_iss * A_BYTES + wave * 1024 + i * 8192); };
+    auto issue_b_one = [&](int i) { load16_to_lds(b_src[i] + kb, smem + B_BASE + b_iss * B_BYTES + wave * 1024 + i * 8192); };
+    auto advance_a = [&]() {
+        ka += BK;
+        a_iss ^= 1;
+    };
+    // the weight K offset jumps at K segment ends (a step never straddles one)
+    auto advance_b = [&]() {
         kb += BK;
         kpos += BK;
         if (kpos == g.kseg_len) { kpos = 0; kb += g.kseg_stride - g.kseg_len; }
-        stage_issue ^= 1;
+        b_iss = (b_iss + 1 == NBUF_B) ? 0 : b_iss + 1;
+    };
+    auto issue_a = [&]() {
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) issue_a_one(i);
+        advance_a();
+    };
+    auto issue_b = [&]() {
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) issue_b_one(i);
+        advance_b();
     };
 
     // fragment addresses: row r = base + (lane & 31), chunk c = 2*ks + (lane >> 5) stored at c ^ key(r)
@@ -200,45 +224,70 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     for (int i = 0; i < 4; ++i) a_off[i] = (wm * 128 + i * 32 + frow) * ROW_BYTES;
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj)
-        b_off[jj] = A_BYTES + ((FUSED_UP ? jj * 128 + wn * 32 : wn * 64 + jj * 32) + frow) * ROW_BYTES;
+        b_off[jj] = ((FUSED_UP ? jj * 128 + wn * 32 : wn * 64 + jj * 32) + frow) * ROW_BYTES;
     int pc[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) pc[ks] = ((ks * 2 + fhalf) ^ fkey) * 16;
 
     bf16x8_t fa[2][4], fb[2][2];
-    auto fetch = [&](int buf, const char *st, int ks) {
+    // fragment r of a 16-wide K group: r < 2 weight rows, else activation rows
+    auto fetch_one = [&](int buf, const char *sa, const char *sb, int ks, int r) {
+        if (r < 2) fb[buf][r] = *(const bf16x8_t *)(sb + b_off[r] + pc[ks]);
+        else fa[buf][r - 2] = *(const bf16x8_t *)(sa + a_off[r - 2] + pc[ks]);
+    };
+    auto fetch = [&](int buf, const char *sa, const char *sb, int ks) {
 #pragma unroll
-        for (int jj = 0; jj < 2; ++jj) fb[buf][jj] = *(const bf16x8_t *)(st + b_off[jj] + pc[ks]);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) fa[buf][i] = *(const bf16x8_t *)(st + a_off[i] + pc[ks]);
+        for (int r = 0; r < 6; ++r) fetch_one(buf, sa, sb, ks, r);
     };
 
     // ---- one K step ---------------------------------------------------------------------------
-    // Before the MFMAs of its last 16-wide K group the workgroup synchronises once: by then every
-    // wavefront has read all of this step's stage (fragments are fetched one group ahead), so the
-    // buffer is handed to the loads of step g + 2; and each wavefront has waited for its own loads
-    // of step g + 1, so after the barrier that stage has landed.  CROSS: fetch the first fragments
-    // of the next step under the last MFMAs (not across a tile boundary).
-    int stage_c = 0;
-    auto step = [&](f32x16_t (&acc)[4][2], auto load_mode, auto cross, bool load_now) {
-        // load_mode 1: always issue the loads (interleaved with the MFMAs); 2: only if load_now
-        constexpr int LOAD_MODE = decltype(load_mode)::value;
-        constexpr bool HAS_LOADS = LOAD_MODE == 1, CROSS = decltype(cross)::value;
-        const char *st = smem + stage_c * STAGE_BYTES;
-        stage_c ^= 1;
-        const char *st_next = smem + stage_c * STAGE_BYTES;
+    // Before the MFMAs of its last 16-wide K group the workgroup synchronises once.  By then every
+    // wavefront has read all of this step's buffers (fragments are fetched one group ahead), so
+    // they are handed to the loads of later steps; and each wavefront has waited for its own loads
+    // of step g + 1, so after the barrier those have landed.  Loads complete in issue order and a
+    // step issues activation loads before weight loads, so "everything but the newest LOADS loads"
+    // (WAIT 1) covers step g + 1 whenever the previous step issued weight loads last; otherwise
+    // the wait is for all loads (WAIT 0).  WAIT 2 picks by `flag`.
+    // A_MODE / B_MODE: 1 issue the operand's loads, 2 only if `flag`, 0 not.  CROSS: fetch the first
+    // fragments of the next step under the last MFMAs (not across a tile boundary).
+    int a_con = 0, b_con = 0;  // buffers the current step reads
+    auto wait_loads = [&](int mode, bool flag) {
+        if (mode == 1 || (mode == 2 && flag)) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    };
+    auto step = [&](f32x16_t (&acc)[4][2], auto a_mode, auto b_mode, auto cross, auto wait_mode, bool flag) {
+        constexpr int A_MODE = decltype(a_mode)::value, B_MODE = decltype(b_mode)::value;
+        constexpr int WAIT = decltype(wait_mode)::value;
+        constexpr bool CROSS = decltype(cross)::value, STEADY = A_MODE == 1 && B_MODE == 1;
+        const char *sa = smem + a_con * A_BYTES, *sb = smem + B_BASE + b_con * B_BYTES;
+        a_con ^= 1;
+        b_con = (b_con + 1 == NBUF_B) ? 0 : b_con + 1;
+        const char *sa_next = smem + a_con * A_BYTES, *sb_next = smem + B_BASE + b_con * B_BYTES;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const int cur = ks & 1, nxt = cur ^ 1;  // KS is even: parity restarts every step
             const bool last = ks == KS - 1;
             if (last) {
-                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                wait_loads(WAIT, flag);
                 asm volatile("s_barrier" ::: "memory");
-                if (HAS_LOADS) issue_loads();
-                if (LOAD_MODE == 2 && load_now) issue_loads();
-                if (CROSS) fetch(nxt, st_next, 0);
+                if (STEADY) {
+                    // program order = issue order wanted: direct loads and fragment reads both touch
+                    // LDS, so the compiler keeps them in this order
+#pragma unroll
+                    for (int r = 0; r < 2 * LOADS; ++r) {
+                        if (r < LOADS) issue_a_one(r);
+                        else issue_b_one(r - LOADS);
+                        if (CROSS && r < 6) fetch_one(nxt, sa_next, sb_next, 0, r);
+                    }
+                    advance_a();
+                    advance_b();
+                } else {
+                    if (A_MODE == 1 || (A_MODE == 2 && flag)) issue_a();
+                    if (B_MODE == 1 || (B_MODE == 2 && flag)) issue_b();
+                    if (CROSS) fetch(nxt, sa_next, sb_next, 0);
+                }
             } else {
-                fetch(nxt, st, ks + 1);
+                fetch(nxt, sa, sb, ks + 1);
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -247,20 +296,14 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
                     acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][jj], fa[cur][i], acc[i][jj], 0, 0, 0);
             // issue order inside a group: the 6 fragment reads of the next group (and, after the
             // barrier, the 2 * LOADS direct-to-LDS loads) are spread between the 8 MFMAs
-            if (last && HAS_LOADS && CROSS) {
+            if (last && STEADY) {
 #pragma unroll
                 for (int r = 0; r < 8; ++r) {
-                    if (r < 2 * LOADS) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // 1 VMEM
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                      // 1 MFMA
-                    if (r < 6) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);           // 1 LDS read
+                    if (r < 2 * LOADS) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);   // 1 VMEM
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // 1 MFMA
+                    if (CROSS && r < 6) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 LDS read
                 }
-            } else if (last && HAS_LOADS) {
-#pragma unroll
-                for (int r = 0; r < 8; ++r) {
-                    if (r < 2 * LOADS) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                }
-            } else if (!last || CROSS) {
+            } else if (!last || (CROSS && A_MODE == 0 && B_MODE == 0)) {
 #pragma unroll
                 for (int r = 0; r < 6; ++r) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
@@ -272,34 +315,40 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
         }
     };
     // the same step for a wavefront with no valid rows in this tile: synchronise and load only
-    auto idle_step = [&](bool has_loads) {
-        stage_c ^= 1;
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    auto idle_step = [&](bool load_a, bool load_b, bool lenient) {
+        a_con ^= 1;
+        b_con = (b_con + 1 == NBUF_B) ? 0 : b_con + 1;
+        wait_loads(2, lenient);
         asm volatile("s_barrier" ::: "memory");
-        if (has_loads) issue_loads();
+        if (load_a) issue_a();
+        if (load_b) issue_b();
     };
     using T_ = std::integral_constant<bool, true>;
     using F_ = std::integral_constant<bool, false>;
-    using ALWAYS_ = std::integral_constant<int, 1>;
-    using MAYBE_ = std::integral_constant<int, 2>;
+    using M0_ = std::integral_constant<int, 0>;
+    using M1_ = std::integral_constant<int, 1>;
+    using M2_ = std::integral_constant<int, 2>;
 
     // ---- epilogue ---------------------------------------------------------------------------------
     // The weight fragment is the MFMA's first operand, so acc[i][jj] holds a transposed 32x32 tile:
     // element v of lane l is (n = 8*(v/4) + 4*(l/32) + v%4, m = l%32), i.e. four consecutive output
     // columns of one row per group of four values.  Per 32-row sub-tile the wavefront packs to
-    // bf16, transposes through its own LDS region (16-byte chunks XOR-swizzled by row) and writes
-    // whole rows with 16-byte stores.
+    // bf16, transposes through LDS (16-byte chunks XOR-swizzled by row) and writes whole rows with
+    // 16-byte stores.  The staging bytes are the four 1 KB pieces of the free weight buffer that this
+    // wavefront's own next weight loads fill, so no other wavefront touches them.
     constexpr int BNW = SH::BNW, ROWB = SH::ROWB;
     constexpr int CH = ROWB / 16;               // 16-byte chunks per staged row
     constexpr int KSH = (ROWB == 128) ? 1 : 2;  // rows per 256 bytes of LDS = 1 << KSH
-    char *stg = smem + NSTAGE * STAGE_BYTES + wave * SH::STG_WAVE;
     const int fhalf8 = fhalf * 8;
+    // byte o of the wavefront's logical 4 KB staging area -> offset inside a weight buffer
+    auto stg_off = [&](int o) { return wave * 1024 + (o >> 10) * 8192 + (o & 1023); };
     auto epilogue = [&](f32x16_t (&acc)[4][2], const Tile &t, int n0, int n_valid) {
         uint16_t *out = (uint16_t *)g.out;
         constexpr int ROWS_PER_IT = 64 / CH;
         const int rr = lane / CH, cc = lane % CH;
         const int ncol = n0 + wn * BNW + cc * 8;
         const int wkey = (frow >> KSH) & (CH - 1);
+        char *stg = smem + B_BASE + b_iss * B_BYTES;  // the buffer read in the tile's last step
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if (i >= n_valid) break;
@@ -313,13 +362,13 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
                         h[r] = gt * __frcp_rn(1.0f + __expf(-gt)) * up;
                     }
                     uint2 pk = make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
-                    *(uint2 *)(stg + frow * ROWB + ((q ^ wkey) * 16) + fhalf8) = pk;
+                    *(uint2 *)(stg + stg_off(frow * ROWB + ((q ^ wkey) * 16) + fhalf8)) = pk;
                 } else {
 #pragma unroll
                     for (int jj = 0; jj < 2; ++jj) {
                         uint2 pk = make_uint2(pack_bf16x2(acc[i][jj][q * 4 + 0], acc[i][jj][q * 4 + 1]),
                                               pack_bf16x2(acc[i][jj][q * 4 + 2], acc[i][jj][q * 4 + 3]));
-                        *(uint2 *)(stg + frow * ROWB + (((jj * 4 + q) ^ wkey) * 16) + fhalf8) = pk;
+                        *(uint2 *)(stg + stg_off(frow * ROWB + (((jj * 4 + q) ^ wkey) * 16) + fhalf8)) = pk;
                     }
                 }
             }
@@ -329,7 +378,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
                 const int ml = it * ROWS_PER_IT + rr;
                 const int row = t.m0 + wm * 128 + i * 32 + ml;
                 const int key = (ml >> KSH) & (CH - 1);
-                const uint4 v = *(const uint4 *)(stg + ml * ROWB + ((cc ^ key) * 16));
+                const uint4 v = *(const uint4 *)(stg + stg_off(ml * ROWB + ((cc ^ key) * 16)));
                 if (row < t.m_end && ncol < g.N) *(uint4 *)(out + (int64_t)row * g.ldo + ncol) = v;
             }
             // LDS operations of one wavefront execute in order: the next sub-tile's writes cannot
@@ -338,13 +387,20 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     };
 
     // ---- tile loop ----------------------------------------------------------------------------------
+    // Per tile of nk steps: steps 0 .. nk-4 load this tile; step nk-3 loads its last activation
+    // step and the next tile's first weight step; steps nk-2 and nk-1 load the next tile's
+    // activation steps 0 and 1 and (nk-2 only) weight step 1; the next tile's weight step 2 is
+    // issued after the epilogue, which stages through that buffer.
     Tile cur = lookup(mt_first + job / n_tiles_n);
     int cur_n0 = (job % n_tiles_n) * BN;
-    set_sources(cur, cur_n0);
-    issue_loads();
-    issue_loads();  // nk >= 2
-    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");  // step 0 landed; the 2 * LOADS loads of step 1 may be in flight
-    static_assert(2 * LOADS == 8, "prologue wait assumes 8 loads per stage and lane");
+    set_a_sources(cur);
+    set_b_sources(cur, cur_n0);
+    issue_a();
+    issue_b();
+    issue_a();
+    issue_b();
+    issue_b();  // nk >= 3
+    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");  // step 0 landed; 3 * LOADS newer loads may be in flight
     asm volatile("s_barrier" ::: "memory");
     for (;;) {
         const int next_job = job + nblk;
@@ -365,20 +421,25 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
                 for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) acc[i][jj][v] = 0.0f;
-            fetch(0, smem + stage_c * STAGE_BYTES, 0);
-            for (int kt = 0; kt + 2 < nk; ++kt) step(acc, ALWAYS_{}, T_{}, true);
-            // the last two steps load the first two steps of the next tile, if there is one
-            if (has_next) set_sources(nxt, nxt_n0);
-            step(acc, MAYBE_{}, T_{}, has_next);
-            step(acc, MAYBE_{}, F_{}, has_next);
+            fetch(0, smem + a_con * A_BYTES, smem + B_BASE + b_con * B_BYTES, 0);
+            for (int kt = 0; kt + 3 < nk; ++kt) step(acc, M1_{}, M1_{}, T_{}, M1_{}, true);
+            if (has_next) set_b_sources(nxt, nxt_n0);
+            step(acc, M1_{}, M2_{}, T_{}, M1_{}, has_next);
+            if (has_next) set_a_sources(nxt);
+            step(acc, M2_{}, M2_{}, T_{}, M2_{}, has_next);
+            step(acc, M2_{}, M0_{}, F_{}, M2_{}, has_next);
             epilogue(acc, cur, cur_n0, n_valid);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // staging reads done before the buffer is refilled
         } else {
-            for (int kt = 0; kt + 2 < nk; ++kt) idle_step(true);
-            if (has_next) set_sources(nxt, nxt_n0);
-            idle_step(has_next);
-            idle_step(has_next);
+            for (int kt = 0; kt + 3 < nk; ++kt) idle_step(true, true, true);
+            if (has_next) set_b_sources(nxt, nxt_n0);
+            idle_step(true, has_next, true);
+            if (has_next) set_a_sources(nxt);
+            idle_step(has_next, has_next, has_next);
+            idle_step(has_next, false, has_next);
         }
         if (!has_next) break;
+        issue_b();  // the next tile's weight step 2
         cur = nxt;
         cur_n0 = nxt_n0;
         job = next_job;
