@@ -134,7 +134,8 @@ size_t grace_workspace_bytes(int32_t T, int32_t E, int32_t k, int32_t I, int32_t
  * locality); local_rank is then only range-checked.
  *
  * DEVICE: logits [T,E] fp32; rr_in [E] or NULL (= zeros); rr_out [E] or NULL,
- * receives (rr_in[e] + requests of e) mod W_e; topk_expert [T,k];
+ * receives (rr_in[e] + requests of e) mod W_e and must not overlap rr_in (the
+ * kernels read rr_in while rr_out is written; GRACE_EINVAL); topk_expert [T,k];
  * topk_weight [T,k] fp32; topk_inst [T,k] instance ids; expert_count [E]
  * requests per expert in this call; ws from grace_workspace_bytes.
  * Limits: 1 <= k <= min(E, GRACE_MAX_TOPK), E == table's E, T*k < 2^31, T >= 0.

@@ -5,6 +5,7 @@
 //   1-3. key_hist / key_scan / key_pos kernels (stable_sort.h): histogram of
 //        instance ids per chunk of 512 assignments, exclusive scans -> inst_off /
 //        rank_off / node_off, stable rank of each assignment -> perm_pos, perm_src
+//        (scan and rank share one launch when there are few chunks)
 //   4. scatter_rows_kernel one block per token: read the token row once, write it
 //                         to its k buffer positions with 16-byte accesses
 #include "bf16.h"
@@ -55,23 +56,12 @@ extern "C" int grace_permute(const grace_table *table, const int32_t *topk_inst,
     const int nchunks = (int)ceil_div(n, PERM_CHUNK);
     int32_t *hist = (int32_t *)ws;
     int32_t *base = (int32_t *)((char *)ws + align_up((size_t)nchunks * I * 4, 256));
-    int nbits = 0;
-    while ((1 << nbits) < I) ++nbits;
-    if (nchunks > 0) {
-        key_hist_kernel<<<nchunks, 64, 0, st>>>(topk_inst, n, I, hist);
-        GRACE_LAUNCH_CHECK("inst_hist_kernel");
-    }
-    key_scan_kernel<<<1, SCAN_THREADS, 0, st>>>(hist, base, nchunks, I, table->R, table->N, table->d_rank_ptr,
-                                                 table->d_node_first_inst, inst_off, rank_off, node_off);
-    GRACE_LAUNCH_CHECK("perm_scan_kernel");
-    if (nchunks > 0) {
-        key_pos_kernel<<<nchunks, 64, 0, st>>>(topk_inst, n, I, base, inst_off, perm_pos, perm_src, nbits, 1);
-        GRACE_LAUNCH_CHECK("perm_pos_kernel");
-        if (x) {
-            scatter_rows_kernel<<<T, 256, 0, st>>>((const uint4 *)x, k, (int)((size_t)d * el / 16), n, perm_pos,
-                                                   (uint4 *)xp);
-            GRACE_LAUNCH_CHECK("scatter_rows_kernel");
-        }
+    const char *failed = stable_sort_launch(topk_inst, n, I, 1, hist, base, table->R, table->N, table->d_rank_ptr,
+                                            table->d_node_first_inst, inst_off, rank_off, node_off, perm_pos, perm_src, st);
+    if (failed) return fail(GRACE_EHIP, "permute: launch of %s failed", failed);
+    if (nchunks > 0 && x) {
+        scatter_rows_kernel<<<T, 256, 0, st>>>((const uint4 *)x, k, (int)((size_t)d * el / 16), n, perm_pos, (uint4 *)xp);
+        GRACE_LAUNCH_CHECK("scatter_rows_kernel");
     }
     return GRACE_OK;
 }

@@ -1,6 +1,8 @@
 // grace_route: top-k gating, per-expert request counter, locality-first replica pick.
 //
-// Three launches, all integer-exact and free of order-dependent atomics:
+// Three launches (two when there are few chunks: every pick block then sums the
+// histograms of the chunks before its own instead of reading a scanned copy), all
+// integer-exact and free of order-dependent atomics:
 //   1. topk_kernel   one wavefront per token: every lane ranks its logits against
 //                    all others by (logit desc, expert id asc) through scalar
 //                    broadcasts, ranks < k are the choices; softmax weights and a
@@ -118,6 +120,14 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *__restr
     for (int i = tid; i < E; i += TOPK_THREADS) chunk_hist[(size_t)chunk * E + i] = hist[i];
 }
 
+// W of Section 4.3's round-robin for expert e: the weight sum of its candidate tier.
+__device__ __forceinline__ uint32_t next_rr(const uint32_t *rr_in, int e, int32_t n, const int32_t *cand_ptr,
+                                            const uint32_t *cand_cum) {
+    const uint32_t W = cand_cum[cand_ptr[e + 1] - 1];
+    const uint64_t c = (uint64_t)(rr_in ? rr_in[e] : 0u) + (uint64_t)(uint32_t)n;
+    return (uint32_t)(c % W);
+}
+
 __global__ __launch_bounds__(SCAN_THREADS) void route_scan_kernel(const int32_t *__restrict__ hist,
                                                                   int32_t *__restrict__ base, int nchunks, int E,
                                                                   const uint32_t *__restrict__ rr_in,
@@ -136,16 +146,19 @@ __global__ __launch_bounds__(SCAN_THREADS) void route_scan_kernel(const int32_t 
         const int32_t n = totals[e];
         expert_count[e] = n;
         if (rr_out) {
-            const uint32_t W = cand_cum[cand_ptr[e + 1] - 1];
-            const uint64_t c = (uint64_t)(rr_in ? rr_in[e] : 0u) + (uint64_t)(uint32_t)n;
-            rr_out[e] = (uint32_t)(c % W);
+            rr_out[e] = next_rr(rr_in, e, n, cand_ptr, cand_cum);
         }
     }
 }
 
+// FOLD = false: chunk_counts is the scanned histogram (requests of each expert before each chunk).
+// FOLD = true: chunk_counts is the raw per-chunk histogram; the block sums the rows before its own,
+// and the last block also writes expert_count and rr_out.
+template <bool FOLD>
 __global__ __launch_bounds__(64) void pick_kernel(const int32_t *__restrict__ topk_expert, int64_t n_assign, int E,
-                                                  int k, const int32_t *__restrict__ chunk_base,
-                                                  const uint32_t *__restrict__ rr_in,
+                                                  int k, const int32_t *__restrict__ chunk_counts, int nchunks,
+                                                  const uint32_t *__restrict__ rr_in, uint32_t *__restrict__ rr_out,
+                                                  int32_t *__restrict__ expert_count,
                                                   const int32_t *__restrict__ cand_ptr,
                                                   const int32_t *__restrict__ cand_g,
                                                   const uint32_t *__restrict__ cand_cum,
@@ -153,7 +166,21 @@ __global__ __launch_bounds__(64) void pick_kernel(const int32_t *__restrict__ to
     __shared__ uint32_t cnt[GRACE_MAX_EXPERTS];
     const int lane = (int)threadIdx.x;
     const int chunk = (int)blockIdx.x;
-    for (int e = lane; e < E; e += 64) cnt[e] = (uint32_t)chunk_base[(size_t)chunk * E + e];
+    if (FOLD) {
+        for (int e = lane; e < E; e += 64) {
+            int32_t before = 0;
+#pragma unroll 8
+            for (int c = 0; c < chunk; ++c) before += chunk_counts[(size_t)c * E + e];
+            cnt[e] = (uint32_t)before;
+            if (chunk == nchunks - 1) {
+                const int32_t n = before + chunk_counts[(size_t)chunk * E + e];
+                expert_count[e] = n;
+                if (rr_out) rr_out[e] = next_rr(rr_in, e, n, cand_ptr, cand_cum);
+            }
+        }
+    } else {
+        for (int e = lane; e < E; e += 64) cnt[e] = (uint32_t)chunk_counts[(size_t)chunk * E + e];
+    }
     __syncthreads();
     const int64_t a0 = (int64_t)chunk * ROUTE_TOKENS_PER_CHUNK * k;
     const int64_t a1 = min(n_assign, a0 + (int64_t)ROUTE_TOKENS_PER_CHUNK * k);
@@ -180,6 +207,10 @@ __global__ __launch_bounds__(64) void pick_kernel(const int32_t *__restrict__ to
     }
 }
 
+// Few chunks: a pick block can afford to sum the histograms before its own.
+constexpr int ROUTE_FOLD_MAX_LOADS = 256;
+inline bool fold_route_scan(int nchunks, int E) { return nchunks >= 1 && (int64_t)nchunks * ((E + 63) / 64) <= ROUTE_FOLD_MAX_LOADS; }
+
 }  // namespace grace
 
 using namespace grace;
@@ -198,6 +229,8 @@ extern "C" int grace_route(const grace_table *table, int32_t local_rank, grace_p
         return fail(GRACE_EINVAL, "route: unknown policy %d", (int)policy);
     if ((int64_t)T * k > INT32_MAX) return fail(GRACE_ESHAPE, "route: T*k exceeds 2^31-1");
     if (!expert_count || !ws) return fail(GRACE_EINVAL, "route: expert_count or ws is null");
+    if (rr_in && rr_out && (uintptr_t)rr_in < (uintptr_t)(rr_out + E) && (uintptr_t)rr_out < (uintptr_t)(rr_in + E))
+        return fail(GRACE_EINVAL, "route: rr_out overlaps rr_in");
     if (T > 0 && (!logits || !topk_expert || !topk_weight || !topk_inst))
         return fail(GRACE_EINVAL, "route: null device pointer");
     hipStream_t st = (hipStream_t)stream;
@@ -215,14 +248,22 @@ extern "C" int grace_route(const grace_table *table, int32_t local_rank, grace_p
         }
         GRACE_LAUNCH_CHECK("topk_kernel");
     }
+    int nbits = 0;
+    while ((1 << nbits) < E) ++nbits;
+    if (fold_route_scan(nchunks, E)) {
+        pick_kernel<true><<<nchunks, 64, 0, st>>>(topk_expert, (int64_t)T * k, E, k, hist, nchunks, rr_in, rr_out,
+                                                  expert_count, cand_ptr, table->d_cand_g, table->d_cand_cum, topk_inst,
+                                                  nbits);
+        GRACE_LAUNCH_CHECK("pick_kernel");
+        return GRACE_OK;
+    }
     route_scan_kernel<<<1, SCAN_THREADS, 0, st>>>(hist, base, nchunks, E, rr_in, rr_out, expert_count, cand_ptr,
                                                   table->d_cand_cum);
     GRACE_LAUNCH_CHECK("route_scan_kernel");
     if (nchunks > 0) {
-        int nbits = 0;
-        while ((1 << nbits) < E) ++nbits;
-        pick_kernel<<<nchunks, 64, 0, st>>>(topk_expert, (int64_t)T * k, E, k, base, rr_in, cand_ptr, table->d_cand_g,
-                                            table->d_cand_cum, topk_inst, nbits);
+        pick_kernel<false><<<nchunks, 64, 0, st>>>(topk_expert, (int64_t)T * k, E, k, base, nchunks, rr_in, rr_out,
+                                                   expert_count, cand_ptr, table->d_cand_g, table->d_cand_cum, topk_inst,
+                                                   nbits);
         GRACE_LAUNCH_CHECK("pick_kernel");
     }
     return GRACE_OK;

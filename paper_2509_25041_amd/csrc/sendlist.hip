@@ -112,19 +112,9 @@ __global__ __launch_bounds__(256) void expand_traffic_kernel(const int32_t *__re
 
 static int sort_by_key(const int32_t *keys, int64_t n, int k, int nkeys, int32_t *hist, int32_t *base, int32_t *off,
                        int32_t *pos, int32_t *tok, hipStream_t st) {
-    const int nchunks = (int)ceil_div(n, PERM_CHUNK);
-    int nbits = 0;
-    while ((1 << nbits) < nkeys) ++nbits;
-    if (nchunks > 0) {
-        key_hist_kernel<<<nchunks, 64, 0, st>>>(keys, n, nkeys, hist);
-        GRACE_LAUNCH_CHECK("key_hist_kernel");
-    }
-    key_scan_kernel<<<1, SCAN_THREADS, 0, st>>>(hist, base, nchunks, nkeys, 0, 0, nullptr, nullptr, off, nullptr, nullptr);
-    GRACE_LAUNCH_CHECK("key_scan_kernel");
-    if (nchunks > 0) {
-        key_pos_kernel<<<nchunks, 64, 0, st>>>(keys, n, nkeys, base, off, pos, tok, nbits, k);
-        GRACE_LAUNCH_CHECK("key_pos_kernel");
-    }
+    const char *failed = stable_sort_launch(keys, n, nkeys, k, hist, base, 0, 0, nullptr, nullptr, off, nullptr, nullptr,
+                                            pos, tok, st);
+    if (failed) return fail(GRACE_EHIP, "send_lists: launch of %s failed", failed);
     return GRACE_OK;
 }
 

@@ -4,6 +4,7 @@
 //   key_scan_kernel   per-key exclusive scan over chunks, exclusive scan over keys
 //   key_pos_kernel    one wavefront per chunk: stable rank of each item among equal
 //                     keys (ballot matching) -> position of every item and its inverse
+//   key_pos_fold_kernel  the last two in one launch when there are few chunks
 // Keys outside [0, nkeys) are skipped (position -1).  No atomics that affect order.
 #pragma once
 #include "common.h"
@@ -71,6 +72,33 @@ static __global__ __launch_bounds__(SCAN_THREADS) void key_scan_kernel(const int
         for (int n = tid; n <= N; n += SCAN_THREADS) node_off[n] = totals[node_first_inst[n]];
 }
 
+// One wavefront ranks the items of its chunk in order: cnt[key] (LDS) holds the position of the
+// next item with that key; equal keys inside a group of 64 items are ranked by ballot matching.
+__device__ __forceinline__ void rank_chunk(const int32_t *__restrict__ keys, int64_t n_items, int nkeys, int32_t *cnt,
+                                           int32_t *__restrict__ perm_pos, int32_t *__restrict__ perm_src, int nbits,
+                                           int src_div, int chunk, int lane) {
+    const int64_t a0 = (int64_t)chunk * PERM_CHUNK;
+    const int64_t a1 = min(n_items, a0 + PERM_CHUNK);
+    const uint64_t lt = lanemask_lt();
+    for (int64_t b = a0; b < a1; b += 64) {
+        const int64_t a = b + lane;
+        const bool in = a < a1;
+        const int g = in ? keys[a] : 0;
+        const bool valid = in && (unsigned)g < (unsigned)nkeys;
+        const uint64_t same = wave_match((uint32_t)g, valid, nbits);
+        if (valid) {
+            const int32_t pos = cnt[g] + (int32_t)__popcll(same & lt);
+            perm_pos[a] = pos;
+            perm_src[pos] = (int32_t)(a / src_div);  // src_div = 1: the item itself; k: its token
+        } else if (in) {
+            perm_pos[a] = -1;  // key outside the table: no row
+        }
+        __syncthreads();
+        if (valid && is_last_of(same)) cnt[g] += (int32_t)__popcll(same);
+        __syncthreads();
+    }
+}
+
 static __global__ __launch_bounds__(64) void key_pos_kernel(const int32_t *__restrict__ topk_inst, int64_t n_assign, int I,
                                                       const int32_t *__restrict__ chunk_base,
                                                       const int32_t *__restrict__ inst_off,
@@ -81,26 +109,90 @@ static __global__ __launch_bounds__(64) void key_pos_kernel(const int32_t *__res
     const int chunk = (int)blockIdx.x;
     for (int i = lane; i < I; i += 64) cnt[i] = inst_off[i] + chunk_base[(size_t)chunk * I + i];
     __syncthreads();
-    const int64_t a0 = (int64_t)chunk * PERM_CHUNK;
-    const int64_t a1 = min(n_assign, a0 + PERM_CHUNK);
-    const uint64_t lt = lanemask_lt();
-    for (int64_t b = a0; b < a1; b += 64) {
-        const int64_t a = b + lane;
-        const bool in = a < a1;
-        const int g = in ? topk_inst[a] : 0;
-        const bool valid = in && (unsigned)g < (unsigned)I;
-        const uint64_t same = wave_match((uint32_t)g, valid, nbits);
-        if (valid) {
-            const int32_t pos = cnt[g] + (int32_t)__popcll(same & lt);
-            perm_pos[a] = pos;
-            perm_src[pos] = (int32_t)(a / src_div);  // src_div = 1: the item itself; k: its token
-        } else if (in) {
-            perm_pos[a] = -1;  // id outside the table: no row
+    rank_chunk(topk_inst, n_assign, I, cnt, perm_pos, perm_src, nbits, src_div, chunk, lane);
+}
+
+// The scan folded into the position kernel, for few chunks: every block derives its offsets from
+// the chunk histograms itself (totals over all chunks -> exclusive scan over keys, plus the counts
+// of the chunks before its own), which saves the single-block scan launch; block 0 also writes
+// the offset outputs.  Work per block grows with nchunks * nkeys, hence the bound below.
+constexpr int FOLD_MAX_LOADS = 256;  // histogram loads per lane a block may spend on its own scan
+inline bool fold_scan(int nchunks, int nkeys) { return nchunks >= 1 && (int64_t)nchunks * ((nkeys + 63) / 64) <= FOLD_MAX_LOADS; }
+
+static __global__ __launch_bounds__(64) void key_pos_fold_kernel(const int32_t *__restrict__ keys, int64_t n_items, int I,
+                                                           const int32_t *__restrict__ chunk_hist, int nchunks, int R,
+                                                           int N, const int32_t *__restrict__ rank_ptr,
+                                                           const int32_t *__restrict__ node_first_inst,
+                                                           int32_t *__restrict__ inst_off, int32_t *__restrict__ rank_off,
+                                                           int32_t *__restrict__ node_off, int32_t *__restrict__ perm_pos,
+                                                           int32_t *__restrict__ perm_src, int nbits, int src_div) {
+    __shared__ int32_t cnt[GRACE_MAX_INSTANCES];
+    __shared__ int32_t off[GRACE_MAX_INSTANCES + 1];
+    const int lane = (int)threadIdx.x;
+    const int chunk = (int)blockIdx.x;
+    int32_t carry = 0;
+    for (int k0 = 0; k0 < I; k0 += 64) {
+        const int key = k0 + lane;
+        int32_t tot = 0, prev = 0;
+        if (key < I) {
+#pragma unroll 8
+            for (int c = 0; c < nchunks; ++c) {
+                const int32_t v = chunk_hist[(size_t)c * I + key];
+                tot += v;
+                prev += (c < chunk) ? v : 0;
+            }
         }
-        __syncthreads();
-        if (valid && is_last_of(same)) cnt[g] += (int32_t)__popcll(same);
-        __syncthreads();
+        int32_t incl = tot;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int32_t v = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += v;
+        }
+        if (key < I) {
+            off[key] = carry + incl - tot;
+            cnt[key] = carry + incl - tot + prev;
+        }
+        carry += __shfl(incl, 63, 64);
     }
+    if (lane == 0) off[I] = carry;
+    __syncthreads();
+    if (chunk == 0) {
+        for (int i = lane; i <= I; i += 64) inst_off[i] = off[i];
+        if (rank_off)
+            for (int r = lane; r <= R; r += 64) rank_off[r] = off[rank_ptr[r]];
+        if (node_off)
+            for (int n = lane; n <= N; n += 64) node_off[n] = off[node_first_inst[n]];
+    }
+    rank_chunk(keys, n_items, I, cnt, perm_pos, perm_src, nbits, src_div, chunk, lane);
+}
+
+// Host side: the launches of one stable counting sort.  hist / base: workspace of nchunks * nkeys
+// ints each.  rank_ptr .. node_off may be null (plain sort: only `off` is produced).
+static inline const char *stable_sort_launch(const int32_t *keys, int64_t n, int nkeys, int src_div, int32_t *hist,
+                                             int32_t *base, int R, int N, const int32_t *rank_ptr,
+                                             const int32_t *node_first_inst, int32_t *off, int32_t *rank_off,
+                                             int32_t *node_off, int32_t *pos, int32_t *src, hipStream_t st) {
+    const int nchunks = (int)ceil_div(n, PERM_CHUNK);
+    int nbits = 0;
+    while ((1 << nbits) < nkeys) ++nbits;
+    if (nchunks > 0) {
+        key_hist_kernel<<<nchunks, 64, 0, st>>>(keys, n, nkeys, hist);
+        if (hipGetLastError() != hipSuccess) return "key_hist_kernel";
+    }
+    if (fold_scan(nchunks, nkeys)) {
+        key_pos_fold_kernel<<<nchunks, 64, 0, st>>>(keys, n, nkeys, hist, nchunks, R, N, rank_ptr, node_first_inst, off,
+                                                    rank_off, node_off, pos, src, nbits, src_div);
+        if (hipGetLastError() != hipSuccess) return "key_pos_fold_kernel";
+        return nullptr;
+    }
+    key_scan_kernel<<<1, SCAN_THREADS, 0, st>>>(hist, base, nchunks, nkeys, R, N, rank_ptr, node_first_inst, off, rank_off,
+                                                 node_off);
+    if (hipGetLastError() != hipSuccess) return "key_scan_kernel";
+    if (nchunks > 0) {
+        key_pos_kernel<<<nchunks, 64, 0, st>>>(keys, n, nkeys, base, off, pos, src, nbits, src_div);
+        if (hipGetLastError() != hipSuccess) return "key_pos_kernel";
+    }
+    return nullptr;
 }
 
 

@@ -176,6 +176,8 @@ def test_empty_call_and_argument_errors():
         a = {**dict(k=cfg.k, local_rank=0), **bad}
         with pytest.raises(grace.GraceError):
             grace.grace_route(table, a["local_rank"], logits, a["k"])
+    with pytest.raises(grace.GraceError):      # the counter may not be updated in place
+        grace.grace_route(table, 0, logits, cfg.k, 1, rin, rin)
     with pytest.raises(grace.GraceError):      # E of the logits differs from the table's
         grace.grace_route(table, 0, torch.zeros((4, cfg.E + 1), device="cuda"), 2)
     with pytest.raises(grace.GraceError):      # 12-byte rows
