@@ -162,6 +162,20 @@ int grace_permute(const grace_table *table, const int32_t *topk_inst, int32_t T,
                   grace_dtype dt, int32_t *perm_pos, int32_t *perm_src, int32_t *inst_off, int32_t *rank_off,
                   int32_t *node_off, void *xp, void *ws, void *stream);
 
+/* ---- grace_route_permute: grace_route then grace_permute in one call ----------
+ * Same arguments, outputs (bit for bit) and errors as grace_route (Section 3,
+ * Section 4.3, Algorithms 3 and 4) followed by grace_permute (Section 5) on its
+ * topk_inst.  Decode-sized batches, which are bound by launch latency, are
+ * handled by one single-workgroup kernel plus the row scatter instead of five
+ * launches: that path is taken when ceil(T / 16) * k <= 256, E <= 256 and the
+ * table has at most 256 instances; every other size runs the two calls.
+ */
+int grace_route_permute(const grace_table *table, int32_t local_rank, grace_policy policy, const float *logits, int32_t T,
+                        int32_t E, int32_t k, int32_t renorm, const uint32_t *rr_in, uint32_t *rr_out,
+                        int32_t *topk_expert, float *topk_weight, int32_t *topk_inst, int32_t *expert_count,
+                        const void *x, int32_t d, grace_dtype dt, int32_t *perm_pos, int32_t *perm_src,
+                        int32_t *inst_off, int32_t *rank_off, int32_t *node_off, void *xp, void *ws, void *stream);
+
 /* ---- grace_send_lists: de-duplicated hierarchical send lists ------------------
  * Section 5: a token routed to several experts on the same destination is
  * transmitted only once.  For the T tokens of local_rank and their instance ids

@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     grace_mfma_sustained,
     grace_permute,
     grace_route,
+    grace_route_permute,
     grace_send_lists,
     grace_shared_ffn,
     grace_table_validate,

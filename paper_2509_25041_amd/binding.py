@@ -17,7 +17,7 @@ _STATUS = {0: "GRACE_OK", -1: "GRACE_EINVAL", -2: "GRACE_ESHAPE", -3: "GRACE_ETA
 
 EXPORTS = ("grace_table_validate", "grace_table_create", "grace_table_destroy", "grace_table_info",
            "grace_table_instances", "grace_table_local_experts", "grace_workspace_bytes", "grace_route",
-           "grace_permute", "grace_send_lists", "grace_expert_ffn", "grace_expert_ffn_up", "grace_expert_ffn_down", "grace_shared_ffn", "grace_combine", "grace_mfma_sustained", "grace_last_error")
+           "grace_permute", "grace_route_permute", "grace_send_lists", "grace_expert_ffn", "grace_expert_ffn_up", "grace_expert_ffn_down", "grace_shared_ffn", "grace_combine", "grace_mfma_sustained", "grace_last_error")
 
 _lib: Optional[C.CDLL] = None
 
@@ -208,6 +208,32 @@ def grace_permute(table: GraceTable, topk_inst: torch.Tensor, x: Optional[torch.
     _check(load_library().grace_permute(table.handle, _dp(topk_inst), T, k, _dp(x), d, dt, _dp(pos), _dp(src), _dp(ioff),
                                         _dp(roff), _dp(noff), _dp(xp) if x is not None else None, _dp(ws), _stream()))
     return pos, src, ioff, roff, noff, xp
+
+
+def grace_route_permute(table: GraceTable, local_rank: int, logits: torch.Tensor, k: int, x: Optional[torch.Tensor],
+                        renorm: int = 1, rr_in: Optional[torch.Tensor] = None, rr_out: Optional[torch.Tensor] = None,
+                        ws: Optional[torch.Tensor] = None, policy: int = GRACE_POLICY_TAR):
+    """grace_route and grace_permute as one call (one single-workgroup kernel for decode-sized batches).
+    -> ((topk_expert, topk_weight, topk_inst, expert_count), (perm_pos, perm_src, inst_off, rank_off, node_off, xp))."""
+    T, E = logits.shape
+    dev = logits.device
+    if logits.dtype != torch.float32:
+        raise ValueError("logits must be float32")
+    i32 = dict(dtype=torch.int32, device=dev)
+    te, tw = torch.empty((T, k), **i32), torch.empty((T, k), dtype=torch.float32, device=dev)
+    ti, cnt = torch.empty((T, k), **i32), torch.empty((E,), **i32)
+    pos, src = torch.empty(T * k, **i32), torch.empty(T * k, **i32)
+    ioff, roff, noff = torch.empty(table.I + 1, **i32), torch.empty(table.R + 1, **i32), torch.empty(table.N + 1, **i32)
+    d, dt, xp = 0, GRACE_BF16, None
+    if x is not None:
+        d, dt = x.shape[1], _dtype_code(x)
+        xp = torch.empty((T * k, d), dtype=x.dtype, device=dev)
+    ws = _ws(ws, grace_workspace_bytes(T, E, max(k, 1), table.I), dev)
+    _check(load_library().grace_route_permute(table.handle, local_rank, policy, _dp(logits), T, E, k, renorm, _dp(rr_in),
+                                              _dp(rr_out), _dp(te), _dp(tw), _dp(ti), _dp(cnt), _dp(x), d, dt, _dp(pos),
+                                              _dp(src), _dp(ioff), _dp(roff), _dp(noff),
+                                              _dp(xp) if x is not None else None, _dp(ws), _stream()))
+    return (te, tw, ti, cnt), (pos, src, ioff, roff, noff, xp)
 
 
 def grace_send_lists(table: GraceTable, local_rank: int, topk_inst: torch.Tensor, ws: Optional[torch.Tensor] = None):

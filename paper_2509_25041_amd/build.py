@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgrace_moe.so")
-SOURCES = ["table.cpp", "route.hip", "permute.hip", "combine.hip", "ffn.hip", "calibrate.hip", "sendlist.hip"]
+SOURCES = ["table.cpp", "route.hip", "permute.hip", "combine.hip", "ffn.hip", "calibrate.hip", "sendlist.hip",
+           "route_permute_small.hip"]
 
 
 def _newest_source_mtime() -> float:

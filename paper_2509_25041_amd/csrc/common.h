@@ -41,6 +41,25 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace grace
 
+struct grace_table;
+
+namespace grace {
+
+// Host-side argument checks of grace_route / grace_permute (shared with the fused call) and the
+// launch of the row scatter.
+int check_route_args(const grace_table *table, int32_t local_rank, grace_policy policy, const float *logits, int32_t T,
+                     int32_t E, int32_t k, const uint32_t *rr_in, const uint32_t *rr_out, const int32_t *topk_expert,
+                     const float *topk_weight, const int32_t *topk_inst, const int32_t *expert_count, const void *ws);
+int check_permute_args(const grace_table *table, const int32_t *topk_inst, int32_t T, int32_t k, const void *x, int32_t d,
+                       grace_dtype dt, const int32_t *perm_pos, const int32_t *perm_src, const int32_t *inst_off,
+                       const int32_t *rank_off, const int32_t *node_off, const void *xp, const void *ws);
+int launch_topk(const float *logits, int T, int E, int k, int renorm, int32_t *topk_expert, float *topk_weight,
+                int32_t *chunk_hist, hipStream_t st);
+int launch_scatter_rows(const void *x, int T, int k, int d, grace_dtype dt, const int32_t *perm_pos, void *xp,
+                        hipStream_t st);
+
+}  // namespace grace
+
 // The opaque table.  Host vectors describe the topology; one device allocation
 // holds the arrays the kernels read.
 struct grace_table {

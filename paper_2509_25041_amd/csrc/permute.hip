@@ -32,11 +32,11 @@ __global__ __launch_bounds__(256) void scatter_rows_kernel(const uint4 *__restri
 
 }  // namespace grace
 
-using namespace grace;
+namespace grace {
 
-extern "C" int grace_permute(const grace_table *table, const int32_t *topk_inst, int32_t T, int32_t k, const void *x,
-                             int32_t d, grace_dtype dt, int32_t *perm_pos, int32_t *perm_src, int32_t *inst_off,
-                             int32_t *rank_off, int32_t *node_off, void *xp, void *ws, void *stream) {
+int check_permute_args(const grace_table *table, const int32_t *topk_inst, int32_t T, int32_t k, const void *x, int32_t d,
+                       grace_dtype dt, const int32_t *perm_pos, const int32_t *perm_src, const int32_t *inst_off,
+                       const int32_t *rank_off, const int32_t *node_off, const void *xp, const void *ws) {
     if (!table) return fail(GRACE_EINVAL, "permute: table is null");
     if (T < 0 || k < 1) return fail(GRACE_EINVAL, "permute: T=%d, k=%d invalid", T, k);
     if ((int64_t)T * k > INT32_MAX) return fail(GRACE_ESHAPE, "permute: T*k exceeds 2^31-1");
@@ -50,6 +50,28 @@ extern "C" int grace_permute(const grace_table *table, const int32_t *topk_inst,
         if (T > 0 && !xp) return fail(GRACE_EINVAL, "permute: xp is null");
         if ((((uintptr_t)x) | ((uintptr_t)xp)) & 15) return fail(GRACE_EINVAL, "permute: x and xp must be 16-byte aligned");
     }
+    return GRACE_OK;
+}
+
+int launch_scatter_rows(const void *x, int T, int k, int d, grace_dtype dt, const int32_t *perm_pos, void *xp,
+                        hipStream_t st) {
+    const size_t el = dt == GRACE_F32 ? 4 : 2;
+    scatter_rows_kernel<<<T, 256, 0, st>>>((const uint4 *)x, k, (int)((size_t)d * el / 16), (int64_t)T * k, perm_pos,
+                                           (uint4 *)xp);
+    GRACE_LAUNCH_CHECK("scatter_rows_kernel");
+    return GRACE_OK;
+}
+
+}  // namespace grace
+
+using namespace grace;
+
+extern "C" int grace_permute(const grace_table *table, const int32_t *topk_inst, int32_t T, int32_t k, const void *x,
+                             int32_t d, grace_dtype dt, int32_t *perm_pos, int32_t *perm_src, int32_t *inst_off,
+                             int32_t *rank_off, int32_t *node_off, void *xp, void *ws, void *stream) {
+    const int rc = check_permute_args(table, topk_inst, T, k, x, d, dt, perm_pos, perm_src, inst_off, rank_off, node_off,
+                                      xp, ws);
+    if (rc != GRACE_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     const int I = table->I;
     const int64_t n = (int64_t)T * k;
@@ -59,9 +81,6 @@ extern "C" int grace_permute(const grace_table *table, const int32_t *topk_inst,
     const char *failed = stable_sort_launch(topk_inst, n, I, 1, hist, base, table->R, table->N, table->d_rank_ptr,
                                             table->d_node_first_inst, inst_off, rank_off, node_off, perm_pos, perm_src, st);
     if (failed) return fail(GRACE_EHIP, "permute: launch of %s failed", failed);
-    if (nchunks > 0 && x) {
-        scatter_rows_kernel<<<T, 256, 0, st>>>((const uint4 *)x, k, (int)((size_t)d * el / 16), n, perm_pos, (uint4 *)xp);
-        GRACE_LAUNCH_CHECK("scatter_rows_kernel");
-    }
+    if (nchunks > 0 && x) return launch_scatter_rows(x, T, k, d, dt, perm_pos, xp, st);
     return GRACE_OK;
 }

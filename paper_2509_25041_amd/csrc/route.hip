@@ -15,27 +15,16 @@
 //                    number c to the candidate of the tier Algorithm 4 selects
 //                    whose cumulative polling-weight interval holds c mod W.
 #include "common.h"
+#include "route_device.h"
 #include "wave_utils.h"
 
 namespace grace {
 
-__device__ __forceinline__ uint32_t ordered_bits(float v) {
-    const uint32_t u = __float_as_uint(v);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-__device__ __forceinline__ float from_ordered_bits(uint32_t o) {
-    return __uint_as_float((o & 0x80000000u) ? (o ^ 0x80000000u) : ~o);
-}
-
 constexpr int TOPK_THREADS = 512;                                   // 8 wavefronts per chunk
 constexpr int TOPK_TOK_PER_WAVE = ROUTE_TOKENS_PER_CHUNK / (TOPK_THREADS / 64);
 
-// One wavefront per token, VPL experts per lane.  Instead of k rounds of
-// arg-max, every lane learns the rank of its own logits: each lane's key is
-// broadcast through a scalar register (v_readlane) and compared against the
-// local keys, so after E broadcasts rank = number of larger keys.  Keys are
-// distinct (they include the expert id), so ranks are a permutation and the
-// expert with rank j < k is the token's j-th choice.
+// One wavefront per token, VPL experts per lane (token_topk); a histogram of the chosen experts per
+// chunk of tokens feeds the request counter.
 template <int VPL>
 __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *__restrict__ logits, int T, int E, int k,
                                                             int renorm, int32_t *__restrict__ topk_expert,
@@ -60,72 +49,21 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *__restr
     for (int i = 0; i < TOPK_TOK_PER_WAVE; ++i) {
         const int t = t_begin + i;
         if (t >= T) break;  // uniform per wavefront
-        float val[VPL];
-        uint64_t key[VPL];
         int rank[VPL];
-#pragma unroll
-        for (int v = 0; v < VPL; ++v) {
-            const int e = lane + 64 * v;
-            float x = raw[i][v];
-            if (x == 0.0f) x = 0.0f;  // -0.0 and +0.0 compare equal: make them the same bits
-            val[v] = x;
-            // larger key wins: value first, then the lower expert id
-            key[v] = (e < E) ? (((uint64_t)ordered_bits(x) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)e)) : 0ull;
-            rank[v] = 0;
-        }
-        // Lanes without an expert hold key 0, which beats nothing, so all 64 lanes of every
-        // register are broadcast unconditionally and the loop unrolls with constant lane ids.
-#pragma unroll
-        for (int u = 0; u < VPL; ++u) {
-#pragma unroll
-            for (int src = 0; src < 64; ++src) {
-                const uint32_t ohi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(key[u] >> 32), src);
-                const uint32_t olo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)key[u], src);
-                const uint64_t other = ((uint64_t)ohi << 32) | olo;
-#pragma unroll
-                for (int v = 0; v < VPL; ++v) rank[v] += (other > key[v]) ? 1 : 0;
-            }
-        }
-        // the maximum logit belongs to the expert of rank 0
-        float mx = 0.0f;
-#pragma unroll
-        for (int v = 0; v < VPL; ++v) {
-            const uint64_t first = __ballot(rank[v] == 0 && lane + 64 * v < E);
-            if (first) mx = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, val[v]), (int)__builtin_ctzll(first)));
-        }
-        float ex[VPL], den = 0.0f, sel = 0.0f;
-#pragma unroll
-        for (int v = 0; v < VPL; ++v) {
-            ex[v] = (lane + 64 * v < E) ? expf(val[v] - mx) : 0.0f;
-            den += ex[v];
-            sel += (rank[v] < k) ? ex[v] : 0.0f;
-        }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            den += __shfl_xor(den, o, 64);
-            sel += __shfl_xor(sel, o, 64);
-        }
-        const float norm = renorm ? sel : den;
+        float weight[VPL];
+        token_topk<VPL>(raw[i], lane, E, k, renorm, rank, weight);
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
             const int e = lane + 64 * v;
             if (e < E && rank[v] < k) {
                 topk_expert[(size_t)t * k + rank[v]] = e;
-                topk_weight[(size_t)t * k + rank[v]] = ex[v] / norm;
+                topk_weight[(size_t)t * k + rank[v]] = weight[v];
                 atomicAdd(&hist[e], 1);
             }
         }
     }
     __syncthreads();
     for (int i = tid; i < E; i += TOPK_THREADS) chunk_hist[(size_t)chunk * E + i] = hist[i];
-}
-
-// W of Section 4.3's round-robin for expert e: the weight sum of its candidate tier.
-__device__ __forceinline__ uint32_t next_rr(const uint32_t *rr_in, int e, int32_t n, const int32_t *cand_ptr,
-                                            const uint32_t *cand_cum) {
-    const uint32_t W = cand_cum[cand_ptr[e + 1] - 1];
-    const uint64_t c = (uint64_t)(rr_in ? rr_in[e] : 0u) + (uint64_t)(uint32_t)n;
-    return (uint32_t)(c % W);
 }
 
 __global__ __launch_bounds__(SCAN_THREADS) void route_scan_kernel(const int32_t *__restrict__ hist,
@@ -194,12 +132,7 @@ __global__ __launch_bounds__(64) void pick_kernel(const int32_t *__restrict__ to
         if (valid) {
             const uint32_t rank = (uint32_t)__popcll(same & lt);
             const uint64_t c = (uint64_t)cnt[e] + rank + (uint64_t)(rr_in ? rr_in[e] : 0u);
-            const int cb = cand_ptr[e], ce = cand_ptr[e + 1];
-            const uint32_t W = cand_cum[ce - 1];
-            const uint32_t q = (c >> 32) ? (uint32_t)(c % W) : ((uint32_t)c % W);
-            int s = cb;
-            while (s < ce - 1 && cand_cum[s] <= q) ++s;
-            topk_inst[a] = cand_g[s];
+            topk_inst[a] = pick_candidate(c, e, cand_ptr, cand_g, cand_cum);
         }
         __syncthreads();
         if (valid && is_last_of(same)) cnt[e] += (uint32_t)__popcll(same);
@@ -213,11 +146,25 @@ inline bool fold_route_scan(int nchunks, int E) { return nchunks >= 1 && (int64_
 
 }  // namespace grace
 
-using namespace grace;
+namespace grace {
 
-extern "C" int grace_route(const grace_table *table, int32_t local_rank, grace_policy policy, const float *logits, int32_t T, int32_t E,
-                           int32_t k, int32_t renorm, const uint32_t *rr_in, uint32_t *rr_out, int32_t *topk_expert,
-                           float *topk_weight, int32_t *topk_inst, int32_t *expert_count, void *ws, void *stream) {
+// Top-k gate of T >= 1 tokens; chunk_hist receives ceil(T / 32) x E expert counts.
+int launch_topk(const float *logits, int T, int E, int k, int renorm, int32_t *topk_expert, float *topk_weight,
+                int32_t *chunk_hist, hipStream_t st) {
+    const int nchunks = (int)ceil_div(T, ROUTE_TOKENS_PER_CHUNK);
+    switch ((E + 63) / 64) {
+        case 1: topk_kernel<1><<<nchunks, TOPK_THREADS, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist); break;
+        case 2: topk_kernel<2><<<nchunks, TOPK_THREADS, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist); break;
+        case 3: topk_kernel<3><<<nchunks, TOPK_THREADS, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist); break;
+        default: topk_kernel<4><<<nchunks, TOPK_THREADS, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist); break;
+    }
+    GRACE_LAUNCH_CHECK("topk_kernel");
+    return GRACE_OK;
+}
+
+int check_route_args(const grace_table *table, int32_t local_rank, grace_policy policy, const float *logits, int32_t T,
+                     int32_t E, int32_t k, const uint32_t *rr_in, const uint32_t *rr_out, const int32_t *topk_expert,
+                     const float *topk_weight, const int32_t *topk_inst, const int32_t *expert_count, const void *ws) {
     if (!table) return fail(GRACE_EINVAL, "route: table is null");
     if (T < 0) return fail(GRACE_EINVAL, "route: T=%d is negative", T);
     if (E != table->E) return fail(GRACE_ESHAPE, "route: E=%d but the table has %d experts", E, table->E);
@@ -233,20 +180,27 @@ extern "C" int grace_route(const grace_table *table, int32_t local_rank, grace_p
         return fail(GRACE_EINVAL, "route: rr_out overlaps rr_in");
     if (T > 0 && (!logits || !topk_expert || !topk_weight || !topk_inst))
         return fail(GRACE_EINVAL, "route: null device pointer");
+    return GRACE_OK;
+}
+
+}  // namespace grace
+
+using namespace grace;
+
+extern "C" int grace_route(const grace_table *table, int32_t local_rank, grace_policy policy, const float *logits, int32_t T, int32_t E,
+                           int32_t k, int32_t renorm, const uint32_t *rr_in, uint32_t *rr_out, int32_t *topk_expert,
+                           float *topk_weight, int32_t *topk_inst, int32_t *expert_count, void *ws, void *stream) {
+    const int rc = check_route_args(table, local_rank, policy, logits, T, E, k, rr_in, rr_out, topk_expert, topk_weight,
+                                    topk_inst, expert_count, ws);
+    if (rc != GRACE_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     const int nchunks = (int)ceil_div(T, ROUTE_TOKENS_PER_CHUNK);
     int32_t *hist = (int32_t *)ws;
     int32_t *base = (int32_t *)((char *)ws + align_up((size_t)nchunks * E * 4, 256));
     const int32_t *cand_ptr = table->d_cand_ptr + (size_t)(policy == GRACE_POLICY_WRR ? table->R : local_rank) * E;
     if (nchunks > 0) {
-        const int vpl = (E + 63) / 64;
-        switch (vpl) {
-            case 1: topk_kernel<1><<<nchunks, TOPK_THREADS, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, hist); break;
-            case 2: topk_kernel<2><<<nchunks, TOPK_THREADS, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, hist); break;
-            case 3: topk_kernel<3><<<nchunks, TOPK_THREADS, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, hist); break;
-            default: topk_kernel<4><<<nchunks, TOPK_THREADS, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, hist); break;
-        }
-        GRACE_LAUNCH_CHECK("topk_kernel");
+        const int rc_topk = launch_topk(logits, T, E, k, renorm, topk_expert, topk_weight, hist, st);
+        if (rc_topk != GRACE_OK) return rc_topk;
     }
     int nbits = 0;
     while ((1 << nbits) < E) ++nbits;

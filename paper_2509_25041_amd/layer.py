@@ -9,7 +9,7 @@ import torch
 
 from .binding import GraceTable, _check, _dtype_code, grace_workspace_bytes, load_library
 
-STAGES = ("route", "permute", "ffn_up", "ffn_down", "shared_ffn", "combine")
+STAGES = ("route", "permute", "route_permute", "ffn_up", "ffn_down", "shared_ffn", "combine")
 
 
 class GraceMoELayer:
@@ -57,6 +57,8 @@ class GraceMoELayer:
         self.dt = _dtype_code(self.xp)
         self.ws = torch.empty(grace_workspace_bytes(T, table.E, k, table.I, d, f, self.n_shared, self.dt),
                               dtype=torch.uint8, device=device)
+        # decode-sized batches: routing and permutation as one call (one single-workgroup kernel)
+        self.single_call_dispatch = (T >= 1 and table.E <= 256 and table.I <= 256 and -(-T // 16) * k <= 256)
         self._key = None
         self._calls: List[Tuple[str, object, tuple]] = []
 
@@ -77,11 +79,18 @@ class GraceMoELayer:
         wg, wu, wd = self.w
         S = wg.shape[0]
         ws = p(self.ws)
-        calls = [
-            ("route", lib.grace_route, (h, lr, self.policy, p(logits), T, self.table.E, k, self.renorm, p(rr_in), p(rr_out), p(te),
-                                        p(tw), p(ti), p(cnt), ws, st)),
-            ("permute", lib.grace_permute, (h, p(ti), T, k, p(x), d, dt, p(pos), p(src), p(ioff), p(roff), p(noff),
-                                            p(self.xp), ws, st)),
+        if self.single_call_dispatch:
+            calls = [("route_permute", lib.grace_route_permute,
+                      (h, lr, self.policy, p(logits), T, self.table.E, k, self.renorm, p(rr_in), p(rr_out), p(te), p(tw),
+                       p(ti), p(cnt), p(x), d, dt, p(pos), p(src), p(ioff), p(roff), p(noff), p(self.xp), ws, st))]
+        else:
+            calls = [
+                ("route", lib.grace_route, (h, lr, self.policy, p(logits), T, self.table.E, k, self.renorm, p(rr_in),
+                                            p(rr_out), p(te), p(tw), p(ti), p(cnt), ws, st)),
+                ("permute", lib.grace_permute, (h, p(ti), T, k, p(x), d, dt, p(pos), p(src), p(ioff), p(roff), p(noff),
+                                                p(self.xp), ws, st)),
+            ]
+        calls += [
             ("ffn_up", lib.grace_expert_ffn_up, (h, lr, p(self.xp), p(ioff), T, k, d, f, dt, p(wg) if S else None,
                                                  p(wu) if S else None, ws, st)),
             ("ffn_down", lib.grace_expert_ffn_down, (h, lr, p(ioff), T, k, d, f, dt, p(wd) if S else None, p(self.y),

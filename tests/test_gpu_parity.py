@@ -136,6 +136,59 @@ def test_send_lists_bit_exact(name, T, local_rank):
     assert (host(rt)[sl.rank_send_ptr[-1]:] == -1).all()      # nothing written past the lists
 
 
+def run_fused(wl, pl, k, local_rank, rr_in=None, renorm=1, with_rows=True, policy=0):
+    table = grace.GraceTable.from_placement(pl)
+    rin = None if rr_in is None else torch.from_numpy(rr_in.view(np.int32)).cuda()
+    rout = torch.empty(pl.E, dtype=torch.int32, device="cuda")
+    x = dev(wl.x) if with_rows else None
+    (te, tw, ti, cnt), (pos, src, ioff, roff, noff, xp) = grace.grace_route_permute(
+        table, local_rank, dev(wl.logits), k, x, renorm, rin, rout, policy=policy)
+    torch.cuda.synchronize()
+    return SimpleNamespace(te=te, tw=tw, ti=ti, cnt=cnt, rout=rout, pos=pos, src=src, ioff=ioff, roff=roff, noff=noff,
+                           xp=xp, x=x)
+
+
+@pytest.mark.parametrize("name,T,local_rank", [
+    ("tiny", None, 0), ("tiny", 1, 1), ("tiny", 15, 3), ("tiny", 17, 2), ("tiny", 2048, 0),   # 2048: single kernel at k=2
+    ("olmoe_decode64", None, 0), ("olmoe_decode512", None, 0), ("olmoe", 100, 2), ("olmoe", 513, 1),
+    ("qwen", 200, 5), ("dsv2lite", 300, 17), ("mixtral", 1000, 6),
+    ("olmoe", None, 0),                                                                   # two-call path
+])
+def test_route_permute_single_call_bit_exact(name, T, local_rank):
+    """grace_route_permute gives the outputs of the two calls, on the single-workgroup path
+    (decode-sized batches) and on the chained path alike."""
+    cfg = CONFIGS[name]
+    wl = make_workload(cfg, T=T)
+    ref = oracle.route_permute(wl.logits, wl.placement, cfg.k, local_rank)
+    g = run_fused(wl, wl.placement, cfg.k, local_rank)
+    check_route_permute(g, ref, wl, cfg.k)
+
+
+def test_route_permute_single_call_carry_policy_and_wide_experts():
+    cfg = CONFIGS["dsv2lite"]
+    wl = make_workload(cfg, T=400)
+    rr_in = np.random.default_rng(7).integers(0, 2 ** 32, size=cfg.E, dtype=np.uint64).astype(np.uint32)
+    rr_in[:4] = [0, 2 ** 32 - 1, 2 ** 31, 5]
+    for policy in (0, 1):
+        ref = oracle.route_permute(wl.logits, wl.placement, cfg.k, 11, renorm=0, rr_in=rr_in, policy=policy)
+        g = run_fused(wl, wl.placement, cfg.k, 11, rr_in=rr_in, renorm=0, with_rows=False, policy=policy)
+        check_route_permute(g, ref, wl, cfg.k)
+    # more than one expert per lane, heavy ties, an instance table that still fits the single kernel
+    rng = np.random.default_rng(3)
+    E, k, T, R = 150, 5, 333, 4
+    hosts = [sorted(rng.choice(R, size=rng.integers(1, 3), replace=False).tolist()) for _ in range(E)]
+    inst_ptr = np.concatenate([[0], np.cumsum([len(h) for h in hosts])]).astype(np.int32)
+    assert inst_ptr[-1] <= 256
+    pl = SimpleNamespace(E=E, R=R, N=2, rank_node=np.array([0, 0, 1, 1], np.int32),
+                         poll_weight=rng.integers(1, 9, size=R).astype(np.uint32), inst_ptr=inst_ptr,
+                         inst_rank=np.concatenate(hosts).astype(np.int32))
+    logits = np.round(rng.standard_normal((T, E)) * 2).astype(np.float32) / 2
+    wl2 = SimpleNamespace(logits=logits, x=rng.standard_normal((T, 8)).astype(np.float32))
+    ref = oracle.route_permute(logits, pl, k, 1)
+    g = run_fused(wl2, pl, k, 1)
+    check_route_permute(g, ref, wl2, k)
+
+
 @pytest.mark.parametrize("E,k,T", [(128, 8, 1500), (200, 5, 700), (256, 64, 300), (8, 8, 100), (3, 1, 129)])
 def test_route_wide_and_degenerate_expert_counts(E, k, T):
     """More than one expert per lane (E > 64), k = E, k = 1, ties everywhere."""
