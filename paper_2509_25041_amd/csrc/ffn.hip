@@ -36,11 +36,12 @@ template <bool FUSED_UP>
 static int launch_gemm(const GemmArgs &g, grace_dtype dt, int64_t m_bound, hipStream_t st, const char *what) {
     if (m_bound <= 0 || g.N <= 0 || g.K <= 0) return GRACE_OK;
     const int n_seg = g.seg_off ? g.S : 1;
-    if (dt == GRACE_BF16 && g.K % pers::BK == 0 && g.kseg_len % pers::BK == 0 && g.K >= pers::MIN_K_STEPS * pers::BK &&
-        n_seg <= pers::MAX_SEGMENTS) {
-        // persistent large-tile kernel: one workgroup per compute unit, 160 KB of dynamic LDS
+    const bool k_ok = g.K % pers::BK == 0 && g.kseg_len % pers::BK == 0 && g.K >= pers::MIN_K_STEPS * pers::BK &&
+                      n_seg <= pers::MAX_SEGMENTS;
+    if (dt == GRACE_BF16 && k_ok) {
         const int n_cu = compute_units();
         if (n_cu <= 0) return fail(GRACE_EHIP, "%s: cannot query the device", what);
+        // persistent large-tile kernel: one workgroup per compute unit, 160 KB of dynamic LDS
         using SH = pers::Shape<FUSED_UP>;
         const int ntn = (g.N + SH::BN - 1) / SH::BN;
         const int grid = pers::grid_blocks(n_cu);

@@ -78,10 +78,6 @@ __device__ __forceinline__ void load16_to_lds(const void *gptr, char *lds_wave_b
     __builtin_amdgcn_global_load_lds((global_void_t *)gptr, (lds_void_t *)lds_wave_base, 16, 0, 0);
 }
 
-struct Tile {
-    int slot, m0, m_end;  // segment, first row, end of the segment
-};
-
 // SEG_PER_LANE: 1 for up to 64 row segments, 4 for up to 256.
 template <bool FUSED_UP, int SEG_PER_LANE>
 __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const GemmArgs g, int n_tiles_n) {
@@ -92,59 +88,10 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar
     const int wm = wave >> 2, wn = wave & 3;
 
-    // ---- segment table in registers: lane l holds segments SEG_PER_LANE * l .. + SEG_PER_LANE - 1 ----
-    int seg_lo[SEG_PER_LANE], seg_hi[SEG_PER_LANE], seg_base[SEG_PER_LANE];
-    int total_mt;
-    {
-        int lane_tiles = 0;
-#pragma unroll
-        for (int q = 0; q < SEG_PER_LANE; ++q) {
-            const int s = lane * SEG_PER_LANE + q;
-            int lo = 0, hi = 0;
-            if (g.seg_off) {
-                if (s < g.S) { lo = g.seg_off[s]; hi = max(lo, g.seg_off[s + 1]); }
-            } else if (s == 0) {
-                hi = g.M_single;
-            }
-            seg_lo[q] = lo;
-            seg_hi[q] = hi;
-            seg_base[q] = lane_tiles;                 // made global below
-            lane_tiles += (hi - lo + BM - 1) / BM;    // hi >= lo
-        }
-        int incl = lane_tiles;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int up = __shfl_up(incl, o, 64);
-            if (lane >= o) incl += up;
-        }
-        const int lane_base = incl - lane_tiles;
-#pragma unroll
-        for (int q = 0; q < SEG_PER_LANE; ++q) seg_base[q] += lane_base;
-        total_mt = __builtin_amdgcn_readlane(incl, 63);
-    }
-    // (slot, first row, segment end) of m-tile mt < total_mt, as scalars
-    auto lookup = [&](int mt) {
-        int slot = 0, m0 = 0, m_end = 0;
-        bool hit = false;
-#pragma unroll
-        for (int q = 0; q < SEG_PER_LANE; ++q) {
-            const int rel = mt - seg_base[q];
-            const int tiles = (seg_hi[q] - seg_lo[q] + BM - 1) / BM;
-            if (rel >= 0 && rel < tiles) {
-                hit = true;
-                slot = lane * SEG_PER_LANE + q;
-                m0 = seg_lo[q] + rel * BM;
-                m_end = seg_hi[q];
-            }
-        }
-        const unsigned long long owners = __ballot(hit);
-        const int src = owners ? __builtin_ctzll(owners) : 0;
-        Tile t;
-        t.slot = __builtin_amdgcn_readlane(slot, src);
-        t.m0 = __builtin_amdgcn_readlane(m0, src);
-        t.m_end = __builtin_amdgcn_readlane(m_end, src);
-        return t;
-    };
+    SegTable<BM, SEG_PER_LANE> segs;
+    segs.init(g, lane);
+    const int total_mt = segs.total;
+    auto lookup = [&](int mt) { return segs.lookup(mt, lane); };
 
     // ---- this workgroup's tiles ------------------------------------------------------------
     const int nblk = (int)gridDim.x / N_XCD;                          // workgroups per XCD
