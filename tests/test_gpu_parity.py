@@ -81,6 +81,7 @@ def check_route_permute(g, ref, wl, k):
     ("mixtral", 2048, 0), ("mixtral", 2048, 5),
     ("qwen", None, 0), ("qwen", 3001, 7),
     ("dsv2lite", None, 0), ("dsv2lite", 5000, 17),
+    ("qwen3moe", None, 0), ("qwen3moe", 1111, 6),
 ])
 def test_route_and_permute_bit_exact(name, T, local_rank):
     cfg = CONFIGS[name]
@@ -404,7 +405,7 @@ def test_graph_replays_match_eager():
 
 
 # ------------------------------------------- full-size configs, sampled outputs --
-@pytest.mark.parametrize("name", ["olmoe", "qwen", "dsv2lite", "mixtral"])
+@pytest.mark.parametrize("name", ["olmoe", "qwen", "dsv2lite", "mixtral", "qwen3moe"])
 def test_full_size_rank_share_sampled(name):
     """BASELINE sizes in the launch configuration bench.py times (one
     GraceMoELayer.forward): integers bit-exact over the whole call, FFN rows and

@@ -80,6 +80,10 @@ CONFIGS: Dict[str, LayerConfig] = {
                                   nodes=2, gpus_per_node=2, n_hot=4, replica_mode="all", seed=5),
     "olmoe_decode512": LayerConfig("olmoe_decode512", T=512, E=64, k=8, d=2048, f=1024, dtype="bf16", zipf_s=1.2,
                                    nodes=2, gpus_per_node=2, n_hot=4, replica_mode="all", seed=6),
+    # the paper's third model shape (Section 6.1: 128 experts, top-8): two experts per lane in the
+    # wavefront top-k; 16 primaries per rank on 2 x 4 ranks, 8 hot experts replicated per node
+    "qwen3moe": LayerConfig("qwen3moe", T=8192, E=128, k=8, d=2048, f=768, dtype="bf16", zipf_s=1.2,
+                            nodes=2, gpus_per_node=4, n_hot=8, replica_mode="per_node", seed=7),
     "dsv2lite": LayerConfig("dsv2lite", T=32768, E=64, k=6, d=2048, f=1408, dtype="bf16", zipf_s=1.2,
                             nodes=4, gpus_per_node=8, n_hot=8, replica_mode="per_node", n_shared=2,
                             drift_block=4096, seed=4),
