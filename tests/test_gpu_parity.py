@@ -333,6 +333,28 @@ def test_whole_layer_every_rank_element_by_element(name):
     assert rel_err(oracle.widen(host(out)), out_ref) <= tol
 
 
+def test_many_tiles_per_workgroup_element_by_element():
+    """More output tiles than compute units, ragged segments: every persistent workgroup walks
+    several tiles (tile switches, partial tiles, idle wavefronts); one rank's share, every element."""
+    cfg = LayerConfig("bf16_many_tiles", T=7000, E=24, k=4, d=192, f=1024, dtype="bf16", zipf_s=1.0, nodes=1,
+                      gpus_per_node=2, n_hot=3, replica_mode="all", seed=21)
+    wl = make_workload(cfg)
+    pl = wl.placement
+    lr = 0
+    ref = oracle.route_permute(wl.logits, pl, cfg.k, lr)
+    table, g = run_route_permute(wl, pl, cfg.k, lr)
+    check_route_permute(g, ref, wl, cfg.k)
+    lo, hi = int(ref.perm.rank_off[lr]), int(ref.perm.rank_off[lr + 1])
+    seg = np.diff(ref.perm.inst_off[ref.order.rank_ptr[lr]:ref.order.rank_ptr[lr + 1] + 1])
+    assert sum(-(-int(m) // 256) for m in seg) * (cfg.f // 128) > 2 * 256      # > 2 tiles per workgroup
+    wg, wu, wd = _stack_dev(wl, table.local_experts(lr))
+    y = grace.grace_expert_ffn(table, lr, g.xp, g.ioff, cfg.T, cfg.k, wg, wu, wd)
+    torch.cuda.synchronize()
+    want = oracle.expert_ffn(ref, oracle.widen(wl.x), cfg.k, [lr], _weights64(wl), threads=8)
+    assert rel_err(oracle.widen(host(y))[lo:hi], want[lo:hi]) <= TOL["bf16"]
+    assert not host(y)[:lo].any() and not host(y)[hi:].any()      # rows of the other rank untouched
+
+
 def test_layer_object_rank_share_matches_oracle():
     cfg = SMALL["bf16_small"]
     wl = make_workload(cfg)
