@@ -11,17 +11,19 @@
 //
 // All 160 KB of LDS hold operand buffers: two for the activation tile and
 // three for the weight tile (32 KB each).  The K loop is flattened over the
-// workgroup's tiles: in step g, once every wavefront has read the buffers of
-// step g, the activation loads of step g + 2 and the weight loads of step
-// g + 3 are issued, whether those steps are in the same tile or the next one.
-// A batch of loads needs longer than one step to land, which a plain double
-// buffer cannot hide; with this split the activation batch is half as large
-// and the weight batch has two steps.  The pipeline never drains between
-// tiles: the first steps of the next tile are in flight while the current
-// tile's accumulators are converted and written out.  The epilogue stages
-// through the weight buffer that was consumed last (each wavefront uses
-// exactly the bytes its own next weight loads will overwrite, and issues those
-// loads after it is done), so it needs no workgroup barrier.
+// workgroup's tiles.  Step g issues the weight loads of step g + 2 spread over
+// its first three 16-wide K groups (their buffer was read in step g - 1) and,
+// after the one barrier of the step, once every wavefront has read the buffers
+// of step g, the activation loads of step g + 2; whether step g + 2 is in the
+// same tile or the next one.  A batch of loads needs longer than one step to
+// land, which a plain double buffer cannot hide; with this split the weight
+// batch has more than a step and a half, the activation batch is half as large,
+// and the loads are spread over the step instead of issued in one burst.  The
+// pipeline never drains between tiles: the first steps of the next tile are in
+// flight while the current tile's accumulators are converted and written out.
+// The epilogue stages through the weight buffer that was read last (each
+// wavefront uses exactly the bytes its own next weight loads will overwrite),
+// so it needs no workgroup barrier.
 //
 // Ragged row segments (one per local expert slot): rows past the end of a
 // segment are clamped to its last row when loading and never stored; a
@@ -30,7 +32,7 @@
 // registers (1 or 4 segments per lane, so at most 256 segments) and finds a
 // tile's segment with a ballot; there is no tile table in memory.
 // Preconditions (checked by the launcher): K and the K segment length are
-// multiples of 64, K >= 192, at most 256 segments, grid a multiple of 8.
+// multiples of 64, K >= 128, at most 256 segments, grid a multiple of 8.
 //
 // Tile order is XCD-aware: workgroups are dealt round-robin to the 8 XCDs, so
 // block b runs on XCD b % 8 (checked with HW_REG_XCC_ID).  Each XCD owns a
@@ -54,7 +56,7 @@ typedef const __attribute__((address_space(1))) void global_void_t;
 constexpr int BM = 256, BROWS = 256, THREADS = 512, N_XCD = 8;
 constexpr int BK = 64, KS = BK / 16;
 constexpr int NBUF_A = 2, NBUF_B = 3;          // LDS buffers per operand
-constexpr int MIN_K_STEPS = 3;
+constexpr int MIN_K_STEPS = 2;
 constexpr int ROW_BYTES = BK * 2;              // one tile row in LDS
 constexpr int CPR = BK / 8;                    // 16-byte chunks per row
 constexpr int ROWS_PER_LOAD = 1024 / ROW_BYTES;  // rows covered by one wavefront-wide 16-byte load
@@ -188,24 +190,20 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     };
 
     // ---- one K step ---------------------------------------------------------------------------
-    // Before the MFMAs of its last 16-wide K group the workgroup synchronises once.  By then every
-    // wavefront has read all of this step's buffers (fragments are fetched one group ahead), so
-    // they are handed to the loads of later steps; and each wavefront has waited for its own loads
-    // of step g + 1, so after the barrier those have landed.  Loads complete in issue order and a
-    // step issues activation loads before weight loads, so "everything but the newest LOADS loads"
-    // (WAIT 1) covers step g + 1 whenever the previous step issued weight loads last; otherwise
-    // the wait is for all loads (WAIT 0).  WAIT 2 picks by `flag`.
-    // A_MODE / B_MODE: 1 issue the operand's loads, 2 only if `flag`, 0 not.  CROSS: fetch the first
-    // fragments of the next step under the last MFMAs (not across a tile boundary).
+    // Weight loads of step g + 2 go out during the first three K groups (two, one, one).  Before the
+    // MFMAs of the last group the workgroup synchronises once: by then every wavefront has read all
+    // of this step's buffers (fragments are fetched one group ahead), so the activation buffer is
+    // handed to the loads of step g + 2, issued right after; and each wavefront has waited for its
+    // own loads of step g + 1, so after the barrier those have landed.  Loads complete in issue
+    // order, so "everything but the newest LOADS loads" covers step g + 1 whenever this step issued
+    // its weight loads; otherwise the wait is for all loads.
+    // LOAD_MODE: 1 issue the loads of step g + 2, 2 only if `flag` (tile boundary without a next
+    // tile).  CROSS: fetch the first fragments of the next step under the last MFMAs (not across a
+    // tile boundary).
     int a_con = 0, b_con = 0;  // buffers the current step reads
-    auto wait_loads = [&](int mode, bool flag) {
-        if (mode == 1 || (mode == 2 && flag)) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-    };
-    auto step = [&](f32x16_t (&acc)[4][2], auto a_mode, auto b_mode, auto cross, auto wait_mode, bool flag) {
-        constexpr int A_MODE = decltype(a_mode)::value, B_MODE = decltype(b_mode)::value;
-        constexpr int WAIT = decltype(wait_mode)::value;
-        constexpr bool CROSS = decltype(cross)::value, STEADY = A_MODE == 1 && B_MODE == 1;
+    auto step = [&](f32x16_t (&acc)[4][2], auto load_mode, auto cross, bool flag) {
+        constexpr int LOAD_MODE = decltype(load_mode)::value;
+        constexpr bool CROSS = decltype(cross)::value, STEADY = LOAD_MODE == 1;
         const char *sa = smem + a_con * A_BYTES, *sb = smem + B_BASE + b_con * B_BYTES;
         a_con ^= 1;
         b_con = (b_con + 1 == NBUF_B) ? 0 : b_con + 1;
@@ -214,47 +212,72 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
         for (int ks = 0; ks < KS; ++ks) {
             const int cur = ks & 1, nxt = cur ^ 1;  // KS is even: parity restarts every step
             const bool last = ks == KS - 1;
-            if (last) {
-                wait_loads(WAIT, flag);
-                asm volatile("s_barrier" ::: "memory");
+            // program order = issue order wanted: direct loads and fragment reads both touch LDS, so
+            // the compiler keeps them in this order
+            if (!last) {
+                const int first_load = ks == 0 ? 0 : ks + 1, n_loads = ks == 0 ? 2 : 1;  // 0,1 | 2 | 3
                 if (STEADY) {
-                    // program order = issue order wanted: direct loads and fragment reads both touch
-                    // LDS, so the compiler keeps them in this order
 #pragma unroll
-                    for (int r = 0; r < 2 * LOADS; ++r) {
-                        if (r < LOADS) issue_a_one(r);
-                        else issue_b_one(r - LOADS);
-                        if (CROSS && r < 6) fetch_one(nxt, sa_next, sb_next, 0, r);
+                    for (int r = 0; r < 6; ++r) {
+                        if (r == 0) issue_b_one(first_load);
+                        if (r == 3 && n_loads == 2) issue_b_one(first_load + 1);
+                        fetch_one(nxt, sa, sb, ks + 1, r);
                     }
-                    advance_a();
-                    advance_b();
                 } else {
-                    if (A_MODE == 1 || (A_MODE == 2 && flag)) issue_a();
-                    if (B_MODE == 1 || (B_MODE == 2 && flag)) issue_b();
-                    if (CROSS) fetch(nxt, sa_next, sb_next, 0);
+                    if (flag) {
+                        issue_b_one(first_load);
+                        if (n_loads == 2) issue_b_one(first_load + 1);
+                    }
+                    fetch(nxt, sa, sb, ks + 1);
                 }
             } else {
-                fetch(nxt, sa, sb, ks + 1);
+                if (STEADY || flag) {
+                    advance_b();
+                    asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
+                } else {
+                    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                }
+                asm volatile("s_barrier" ::: "memory");
+                if (STEADY) {
+#pragma unroll
+                    for (int r = 0; r < 6; ++r) {
+                        if (r < LOADS) issue_a_one(r);
+                        if (CROSS) fetch_one(nxt, sa_next, sb_next, 0, r);
+                    }
+                    advance_a();
+                } else {
+                    if (flag) issue_a();
+                    if (CROSS) fetch(nxt, sa_next, sb_next, 0);
+                }
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int jj = 0; jj < 2; ++jj)
                     acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][jj], fa[cur][i], acc[i][jj], 0, 0, 0);
-            // issue order inside a group: the 6 fragment reads of the next group (and, after the
-            // barrier, the 2 * LOADS direct-to-LDS loads) are spread between the 8 MFMAs
-            if (last && STEADY) {
-#pragma unroll
-                for (int r = 0; r < 8; ++r) {
-                    if (r < 2 * LOADS) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);   // 1 VMEM
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // 1 MFMA
-                    if (CROSS && r < 6) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 LDS read
-                }
-            } else if (!last || (CROSS && A_MODE == 0 && B_MODE == 0)) {
+            // issue order inside a group: the fragment reads of the next group and the direct-to-LDS
+            // loads are spread between the 8 MFMAs
+            if (STEADY && !last) {
 #pragma unroll
                 for (int r = 0; r < 6; ++r) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 LDS read
+                    if (r == 0 || (r == 3 && ks == 0)) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // 1 VMEM
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                     // 1 MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                     // 1 LDS read
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            } else if (STEADY && last) {
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    if (r < LOADS) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    if (CROSS && r < 6) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+            } else if (!last) {
+                // tile boundary: the conditional loads sit in a basic block of their own
+#pragma unroll
+                for (int r = 0; r < 6; ++r) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 }
                 __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
             }
@@ -262,17 +285,20 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
         }
     };
     // the same step for a wavefront with no valid rows in this tile: synchronise and load only
-    auto idle_step = [&](bool load_a, bool load_b, bool lenient) {
+    auto idle_step = [&](bool loads_on) {
         a_con ^= 1;
         b_con = (b_con + 1 == NBUF_B) ? 0 : b_con + 1;
-        wait_loads(2, lenient);
+        if (loads_on) {
+            issue_b();
+            asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        }
         asm volatile("s_barrier" ::: "memory");
-        if (load_a) issue_a();
-        if (load_b) issue_b();
+        if (loads_on) issue_a();
     };
     using T_ = std::integral_constant<bool, true>;
     using F_ = std::integral_constant<bool, false>;
-    using M0_ = std::integral_constant<int, 0>;
     using M1_ = std::integral_constant<int, 1>;
     using M2_ = std::integral_constant<int, 2>;
 
@@ -334,10 +360,8 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     };
 
     // ---- tile loop ----------------------------------------------------------------------------------
-    // Per tile of nk steps: steps 0 .. nk-4 load this tile; step nk-3 loads its last activation
-    // step and the next tile's first weight step; steps nk-2 and nk-1 load the next tile's
-    // activation steps 0 and 1 and (nk-2 only) weight step 1; the next tile's weight step 2 is
-    // issued after the epilogue, which stages through that buffer.
+    // Per tile of nk steps: steps 0 .. nk-3 load this tile's steps 2 .. nk-1; steps nk-2 and nk-1
+    // load steps 0 and 1 of the next tile, if there is one.
     Tile cur = lookup(mt_first + job / n_tiles_n);
     int cur_n0 = (job % n_tiles_n) * BN;
     set_a_sources(cur);
@@ -345,9 +369,8 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     issue_a();
     issue_b();
     issue_a();
-    issue_b();
-    issue_b();  // nk >= 3
-    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");  // step 0 landed; 3 * LOADS newer loads may be in flight
+    issue_b();  // nk >= 2
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");  // step 0 landed; the 2 * LOADS loads of step 1 may be in flight
     asm volatile("s_barrier" ::: "memory");
     for (;;) {
         const int next_job = job + nblk;
@@ -369,24 +392,25 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
 #pragma unroll
                     for (int v = 0; v < 16; ++v) acc[i][jj][v] = 0.0f;
             fetch(0, smem + a_con * A_BYTES, smem + B_BASE + b_con * B_BYTES, 0);
-            for (int kt = 0; kt + 3 < nk; ++kt) step(acc, M1_{}, M1_{}, T_{}, M1_{}, true);
-            if (has_next) set_b_sources(nxt, nxt_n0);
-            step(acc, M1_{}, M2_{}, T_{}, M1_{}, has_next);
-            if (has_next) set_a_sources(nxt);
-            step(acc, M2_{}, M2_{}, T_{}, M2_{}, has_next);
-            step(acc, M2_{}, M0_{}, F_{}, M2_{}, has_next);
+            for (int kt = 0; kt + 2 < nk; ++kt) step(acc, M1_{}, T_{}, true);
+            if (has_next) {
+                set_a_sources(nxt);
+                set_b_sources(nxt, nxt_n0);
+            }
+            step(acc, M2_{}, T_{}, has_next);
+            step(acc, M2_{}, F_{}, has_next);
             epilogue(acc, cur, cur_n0, n_valid);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // staging reads done before the buffer is refilled
         } else {
-            for (int kt = 0; kt + 3 < nk; ++kt) idle_step(true, true, true);
-            if (has_next) set_b_sources(nxt, nxt_n0);
-            idle_step(true, has_next, true);
-            if (has_next) set_a_sources(nxt);
-            idle_step(has_next, has_next, has_next);
-            idle_step(has_next, false, has_next);
+            for (int kt = 0; kt + 2 < nk; ++kt) idle_step(true);
+            if (has_next) {
+                set_a_sources(nxt);
+                set_b_sources(nxt, nxt_n0);
+            }
+            idle_step(has_next);
+            idle_step(has_next);
         }
         if (!has_next) break;
-        issue_b();  // the next tile's weight step 2
         cur = nxt;
         cur_n0 = nxt_n0;
         job = next_job;
