@@ -1,4 +1,5 @@
-// bf16 <-> fp32 conversions on raw bits (round-to-nearest-even on narrowing).
+// bf16 <-> fp32 conversions (round-to-nearest-even on narrowing).  Pairs are narrowed with the
+// packed hardware conversion of gfx950 (v_cvt_pk_bf16_f32), one instruction per two values.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -27,8 +28,13 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
     u += 0x7FFFu + ((u >> 16) & 1u);
     return u >> 16;
 }
+typedef __bf16 bf16x2_native __attribute__((ext_vector_type(2)));
+typedef float f32x2_native __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+    f32x2_native v;
+    v.x = lo;
+    v.y = hi;
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_native));
 }
 
 __device__ __forceinline__ void unpack_bf16x8(const uint4 &v, float *f) {
