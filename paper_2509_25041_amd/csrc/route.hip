@@ -92,34 +92,46 @@ __global__ __launch_bounds__(SCAN_THREADS) void route_scan_kernel(const int32_t 
 // FOLD = false: chunk_counts is the scanned histogram (requests of each expert before each chunk).
 // FOLD = true: chunk_counts is the raw per-chunk histogram; the block sums the rows before its own,
 // and the last block also writes expert_count and rr_out.
+constexpr int PICK_THREADS = 256;  // wavefront 0 ranks; all four sum histogram rows when FOLD
+
 template <bool FOLD>
-__global__ __launch_bounds__(64) void pick_kernel(const int32_t *__restrict__ topk_expert, int64_t n_assign, int E,
-                                                  int k, const int32_t *__restrict__ chunk_counts, int nchunks,
-                                                  const uint32_t *__restrict__ rr_in, uint32_t *__restrict__ rr_out,
-                                                  int32_t *__restrict__ expert_count,
-                                                  const int32_t *__restrict__ cand_ptr,
-                                                  const int32_t *__restrict__ cand_g,
-                                                  const uint32_t *__restrict__ cand_cum,
-                                                  int32_t *__restrict__ topk_inst, int nbits) {
+__global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__restrict__ topk_expert, int64_t n_assign,
+                                                            int E, int k, const int32_t *__restrict__ chunk_counts,
+                                                            int nchunks, const uint32_t *__restrict__ rr_in,
+                                                            uint32_t *__restrict__ rr_out,
+                                                            int32_t *__restrict__ expert_count,
+                                                            const int32_t *__restrict__ cand_ptr,
+                                                            const int32_t *__restrict__ cand_g,
+                                                            const uint32_t *__restrict__ cand_cum,
+                                                            int32_t *__restrict__ topk_inst, int nbits) {
     __shared__ uint32_t cnt[GRACE_MAX_EXPERTS];
-    const int lane = (int)threadIdx.x;
+    const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int chunk = (int)blockIdx.x;
     if (FOLD) {
+        // requests before this chunk: the wavefronts share the histogram rows 0 .. chunk-1
+        for (int e = tid; e < E; e += PICK_THREADS) cnt[e] = 0;
+        __syncthreads();
         for (int e = lane; e < E; e += 64) {
-            int32_t before = 0;
+            int32_t part = 0;
 #pragma unroll 8
-            for (int c = 0; c < chunk; ++c) before += chunk_counts[(size_t)c * E + e];
-            cnt[e] = (uint32_t)before;
-            if (chunk == nchunks - 1) {
-                const int32_t n = before + chunk_counts[(size_t)chunk * E + e];
+            for (int c = wave; c < chunk; c += PICK_THREADS / 64) part += chunk_counts[(size_t)c * E + e];
+            if (part) atomicAdd(&cnt[e], (uint32_t)part);  // integer sum: order does not matter
+        }
+        __syncthreads();
+        if (chunk == nchunks - 1) {
+            for (int e = tid; e < E; e += PICK_THREADS) {
+                const int32_t n = (int32_t)cnt[e] + chunk_counts[(size_t)chunk * E + e];
                 expert_count[e] = n;
                 if (rr_out) rr_out[e] = next_rr(rr_in, e, n, cand_ptr, cand_cum);
             }
         }
     } else {
-        for (int e = lane; e < E; e += 64) cnt[e] = (uint32_t)chunk_counts[(size_t)chunk * E + e];
+        for (int e = tid; e < E; e += PICK_THREADS) cnt[e] = (uint32_t)chunk_counts[(size_t)chunk * E + e];
+        __syncthreads();
     }
-    __syncthreads();
+    if (wave != 0) return;
+    // One wavefront walks the chunk in order.  Its LDS operations execute in program order, so a
+    // counter updated by the last lane of a match set is seen by the next group of 64 assignments.
     const int64_t a0 = (int64_t)chunk * ROUTE_TOKENS_PER_CHUNK * k;
     const int64_t a1 = min(n_assign, a0 + (int64_t)ROUTE_TOKENS_PER_CHUNK * k);
     const uint64_t lt = lanemask_lt();
@@ -134,9 +146,7 @@ __global__ __launch_bounds__(64) void pick_kernel(const int32_t *__restrict__ to
             const uint64_t c = (uint64_t)cnt[e] + rank + (uint64_t)(rr_in ? rr_in[e] : 0u);
             topk_inst[a] = pick_candidate(c, e, cand_ptr, cand_g, cand_cum);
         }
-        __syncthreads();
         if (valid && is_last_of(same)) cnt[e] += (uint32_t)__popcll(same);
-        __syncthreads();
     }
 }
 
@@ -205,7 +215,7 @@ extern "C" int grace_route(const grace_table *table, int32_t local_rank, grace_p
     int nbits = 0;
     while ((1 << nbits) < E) ++nbits;
     if (fold_route_scan(nchunks, E)) {
-        pick_kernel<true><<<nchunks, 64, 0, st>>>(topk_expert, (int64_t)T * k, E, k, hist, nchunks, rr_in, rr_out,
+        pick_kernel<true><<<nchunks, PICK_THREADS, 0, st>>>(topk_expert, (int64_t)T * k, E, k, hist, nchunks, rr_in, rr_out,
                                                   expert_count, cand_ptr, table->d_cand_g, table->d_cand_cum, topk_inst,
                                                   nbits);
         GRACE_LAUNCH_CHECK("pick_kernel");
@@ -215,7 +225,7 @@ extern "C" int grace_route(const grace_table *table, int32_t local_rank, grace_p
                                                   table->d_cand_cum);
     GRACE_LAUNCH_CHECK("route_scan_kernel");
     if (nchunks > 0) {
-        pick_kernel<false><<<nchunks, 64, 0, st>>>(topk_expert, (int64_t)T * k, E, k, base, nchunks, rr_in, rr_out,
+        pick_kernel<false><<<nchunks, PICK_THREADS, 0, st>>>(topk_expert, (int64_t)T * k, E, k, base, nchunks, rr_in, rr_out,
                                                    expert_count, cand_ptr, table->d_cand_g, table->d_cand_cum, topk_inst,
                                                    nbits);
         GRACE_LAUNCH_CHECK("pick_kernel");

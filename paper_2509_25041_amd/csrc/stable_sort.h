@@ -74,6 +74,8 @@ static __global__ __launch_bounds__(SCAN_THREADS) void key_scan_kernel(const int
 
 // One wavefront ranks the items of its chunk in order: cnt[key] (LDS) holds the position of the
 // next item with that key; equal keys inside a group of 64 items are ranked by ballot matching.
+// The LDS operations of one wavefront execute in program order, so a counter updated by the last
+// lane of a match set is seen by the next group of 64 items without a barrier.
 __device__ __forceinline__ void rank_chunk(const int32_t *__restrict__ keys, int64_t n_items, int nkeys, int32_t *cnt,
                                            int32_t *__restrict__ perm_pos, int32_t *__restrict__ perm_src, int nbits,
                                            int src_div, int chunk, int lane) {
@@ -93,9 +95,7 @@ __device__ __forceinline__ void rank_chunk(const int32_t *__restrict__ keys, int
         } else if (in) {
             perm_pos[a] = -1;  // key outside the table: no row
         }
-        __syncthreads();
         if (valid && is_last_of(same)) cnt[g] += (int32_t)__popcll(same);
-        __syncthreads();
     }
 }
 
@@ -119,29 +119,39 @@ static __global__ __launch_bounds__(64) void key_pos_kernel(const int32_t *__res
 constexpr int FOLD_MAX_LOADS = 256;  // histogram loads per lane a block may spend on its own scan
 inline bool fold_scan(int nchunks, int nkeys) { return nchunks >= 1 && (int64_t)nchunks * ((nkeys + 63) / 64) <= FOLD_MAX_LOADS; }
 
-static __global__ __launch_bounds__(64) void key_pos_fold_kernel(const int32_t *__restrict__ keys, int64_t n_items, int I,
-                                                           const int32_t *__restrict__ chunk_hist, int nchunks, int R,
-                                                           int N, const int32_t *__restrict__ rank_ptr,
-                                                           const int32_t *__restrict__ node_first_inst,
-                                                           int32_t *__restrict__ inst_off, int32_t *__restrict__ rank_off,
-                                                           int32_t *__restrict__ node_off, int32_t *__restrict__ perm_pos,
-                                                           int32_t *__restrict__ perm_src, int nbits, int src_div) {
-    __shared__ int32_t cnt[GRACE_MAX_INSTANCES];
-    __shared__ int32_t off[GRACE_MAX_INSTANCES + 1];
-    const int lane = (int)threadIdx.x;
+constexpr int POS_FOLD_THREADS = 256;  // all four wavefronts sum histogram rows; wavefront 0 scans and ranks
+
+static __global__ __launch_bounds__(POS_FOLD_THREADS) void key_pos_fold_kernel(
+    const int32_t *__restrict__ keys, int64_t n_items, int I, const int32_t *__restrict__ chunk_hist, int nchunks, int R,
+    int N, const int32_t *__restrict__ rank_ptr, const int32_t *__restrict__ node_first_inst,
+    int32_t *__restrict__ inst_off, int32_t *__restrict__ rank_off, int32_t *__restrict__ node_off,
+    int32_t *__restrict__ perm_pos, int32_t *__restrict__ perm_src, int nbits, int src_div) {
+    __shared__ int32_t cnt[GRACE_MAX_INSTANCES];      // items of each key in the chunks before this one, then positions
+    __shared__ int32_t off[GRACE_MAX_INSTANCES + 1];  // items of each key in all chunks, then exclusive offsets
+    const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int chunk = (int)blockIdx.x;
+    for (int i = tid; i < I; i += POS_FOLD_THREADS) {
+        cnt[i] = 0;
+        off[i] = 0;
+    }
+    __syncthreads();
+    for (int key = lane; key < I; key += 64) {
+        int32_t tot = 0, prev = 0;
+#pragma unroll 8
+        for (int c = wave; c < nchunks; c += POS_FOLD_THREADS / 64) {
+            const int32_t v = chunk_hist[(size_t)c * I + key];
+            tot += v;
+            prev += (c < chunk) ? v : 0;
+        }
+        if (tot) atomicAdd(&off[key], tot);  // integer sums: order does not matter
+        if (prev) atomicAdd(&cnt[key], prev);
+    }
+    __syncthreads();
+    if (wave != 0) return;
     int32_t carry = 0;
     for (int k0 = 0; k0 < I; k0 += 64) {
         const int key = k0 + lane;
-        int32_t tot = 0, prev = 0;
-        if (key < I) {
-#pragma unroll 8
-            for (int c = 0; c < nchunks; ++c) {
-                const int32_t v = chunk_hist[(size_t)c * I + key];
-                tot += v;
-                prev += (c < chunk) ? v : 0;
-            }
-        }
+        const int32_t tot = key < I ? off[key] : 0;
         int32_t incl = tot;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
@@ -150,12 +160,11 @@ static __global__ __launch_bounds__(64) void key_pos_fold_kernel(const int32_t *
         }
         if (key < I) {
             off[key] = carry + incl - tot;
-            cnt[key] = carry + incl - tot + prev;
+            cnt[key] += carry + incl - tot;
         }
         carry += __shfl(incl, 63, 64);
     }
     if (lane == 0) off[I] = carry;
-    __syncthreads();
     if (chunk == 0) {
         for (int i = lane; i <= I; i += 64) inst_off[i] = off[i];
         if (rank_off)
@@ -180,7 +189,7 @@ static inline const char *stable_sort_launch(const int32_t *keys, int64_t n, int
         if (hipGetLastError() != hipSuccess) return "key_hist_kernel";
     }
     if (fold_scan(nchunks, nkeys)) {
-        key_pos_fold_kernel<<<nchunks, 64, 0, st>>>(keys, n, nkeys, hist, nchunks, R, N, rank_ptr, node_first_inst, off,
+        key_pos_fold_kernel<<<nchunks, POS_FOLD_THREADS, 0, st>>>(keys, n, nkeys, hist, nchunks, R, N, rank_ptr, node_first_inst, off,
                                                     rank_off, node_off, pos, src, nbits, src_div);
         if (hipGetLastError() != hipSuccess) return "key_pos_fold_kernel";
         return nullptr;
