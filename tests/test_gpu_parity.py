@@ -92,6 +92,18 @@ def test_route_and_permute_bit_exact(name, T, local_rank):
     check_route_permute(g, ref, wl, cfg.k)
 
 
+def test_route_and_permute_many_chunks_separate_scan_kernels():
+    """Enough chunks that the scans run as kernels of their own instead of inside the pick /
+    position kernels (route: > 1024 chunk rows per expert column; permute likewise)."""
+    cfg = LayerConfig("many_chunks", T=50000, E=128, k=8, d=8, f=16, dtype="f32", zipf_s=1.2, nodes=2,
+                      gpus_per_node=4, n_hot=8, replica_mode="per_node", seed=31)
+    wl = make_workload(cfg)
+    assert -(-cfg.T // 32) * 2 > 1024 and -(-cfg.T * cfg.k // 512) * -(-wl.placement.I // 64) > 1024
+    ref = oracle.route_permute(wl.logits, wl.placement, cfg.k, 3)
+    _, g = run_route_permute(wl, wl.placement, cfg.k, 3)
+    check_route_permute(g, ref, wl, cfg.k)
+
+
 def test_route_rr_carry_and_no_renorm():
     cfg = CONFIGS["dsv2lite"]
     wl = make_workload(cfg, T=3000)
