@@ -76,8 +76,15 @@ static_assert(LOADS == 4 && 32 * 128 <= LOADS * 1024, "a wavefront's share of a 
 
 __device__ __forceinline__ int swizzle_key(int row) { return (row >> 1) & (CPR - 1); }
 
-__device__ __forceinline__ void load16_to_lds(const void *gptr, char *lds_wave_base) {
-    __builtin_amdgcn_global_load_lds((global_void_t *)gptr, (lds_void_t *)lds_wave_base, 16, 0, 0);
+// Direct-to-LDS load of 16 bytes per lane: lane l reads base + voff and its data lands at
+// lds_wave_base + 16 * l.  `base` and `lds_wave_base` are uniform.  Issued as inline assembly
+// (the instruction the compiler's own builtin emits, LDS address in M0): the compiler then does
+// not count the load against the LDS counter, and the fragment reads around it keep their exact
+// per-read waits instead of "wait for everything".  The waits for these loads are explicit
+// s_waitcnt vmcnt(N) in the K loop.
+__device__ __forceinline__ void load16_to_lds(const char *base, uint32_t voff, char *lds_wave_base) {
+    const uint32_t lds_addr = (uint32_t)(size_t)(__attribute__((address_space(3))) char *)lds_wave_base;
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0" ::"s"(base), "v"(voff), "s"(lds_addr) : "memory");
 }
 
 // SEG_PER_LANE: 1 for up to 64 row segments, 4 for up to 256.
@@ -104,55 +111,64 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     int job = bslot;
     if (job >= njobs) return;
 
-    const uint16_t *A = (const uint16_t *)g.A;
     const int nk = g.K / BK;
 
-    // ---- this lane's load sources (fixed rows of the current load tile, advancing along K) ----
+    // ---- load sources: a scalar base per operand (advancing along K) + a 32-bit byte offset per lane ----
     // One wavefront-wide load fills 1 KB of LDS = ROWS_PER_LOAD consecutive tile rows; lane l
-    // lands at row l / CPR, chunk position l % CPR.
-    const int lrow = lane / CPR, lpos = lane % CPR;
-    const uint16_t *a_src[LOADS], *b_src[LOADS];
-    int64_t kb = 0;
-    int kpos = 0, ka = 0;
+    // lands at row l / CPR, chunk position l % CPR.  Loads 0, 1 of the fused weight tile read the
+    // gate matrix, loads 2, 3 the up matrix (tile rows 128 .. 255).
+    // Lane-dependent values that are only needed at tile boundaries are recomputed there from an
+    // opaque copy of the lane id: kept live across the K loop they would be spilled to scratch.
+    auto opaque_lane = [&]() {
+        int l = lane;
+        asm volatile("" : "+v"(l));
+        return l;
+    };
+    const char *a_ptr = nullptr, *b_ptr0 = nullptr, *b_ptr1 = nullptr;  // uniform
+    uint32_t a_voff[LOADS], b_voff[LOADS];
+    int kpos = 0;
     int a_iss = 0, b_iss = 0;  // buffers the next loads go to
     auto set_a_sources = [&](const Tile &t) {
+        const int ll = opaque_lane(), lrow = ll / CPR, lpos = ll % CPR;
+        a_ptr = (const char *)g.A + (int64_t)t.m0 * g.lda * 2;
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
             const int tr = (i * 8 + wave) * ROWS_PER_LOAD + lrow;  // tile row
             const int gchunk = lpos ^ swizzle_key(tr);               // global chunk that lands at position lpos
-            const int m = min(t.m0 + tr, t.m_end - 1);
-            a_src[i] = A + (int64_t)m * g.lda + gchunk * 8;
+            const int m = min(tr, t.m_end - 1 - t.m0);
+            a_voff[i] = (uint32_t)m * (uint32_t)(g.lda * 2) + (uint32_t)gchunk * 16u;
         }
-        ka = 0;
     };
     auto set_b_sources = [&](const Tile &t, int n0) {
-        const uint16_t *B0 = (const uint16_t *)g.B0 + (int64_t)t.slot * g.b_slot_stride;
-        const uint16_t *B1 = FUSED_UP ? (const uint16_t *)g.B1 + (int64_t)t.slot * g.b_slot_stride : nullptr;
+        const int64_t first = ((int64_t)t.slot * g.b_slot_stride + (int64_t)n0 * g.ldb) * 2;
+        b_ptr0 = (const char *)g.B0 + first;
+        b_ptr1 = FUSED_UP ? (const char *)g.B1 + first : b_ptr0;
+        const int ll = opaque_lane(), lrow = ll / CPR, lpos = ll % CPR;
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
             const int tr = (i * 8 + wave) * ROWS_PER_LOAD + lrow;
             const int gchunk = lpos ^ swizzle_key(tr);
-            int n;
-            const uint16_t *Bm;
-            if (FUSED_UP) { n = n0 + (tr & 127); Bm = (tr >> 7) ? B1 : B0; }
-            else { n = n0 + tr; Bm = B0; }
-            n = min(n, g.N - 1);
-            b_src[i] = Bm + (int64_t)n * g.ldb + gchunk * 8;
+            const int n = min(FUSED_UP ? (tr & 127) : tr, g.N - 1 - n0);  // n0 < N
+            b_voff[i] = (uint32_t)n * (uint32_t)(g.ldb * 2) + (uint32_t)gchunk * 16u;
         }
-        kb = 0;
         kpos = 0;
     };
-    auto issue_a_one = [&](int i) { load16_to_lds(a_src[i] + ka, smem + a_iss * A_BYTES + wave * 1024 + i * 8192); };
-    auto issue_b_one = [&](int i) { load16_to_lds(b_src[i] + kb, smem + B_BASE + b_iss * B_BYTES + wave * 1024 + i * 8192); };
+    auto issue_a_one = [&](int i) { load16_to_lds(a_ptr, a_voff[i], smem + a_iss * A_BYTES + wave * 1024 + i * 8192); };
+    auto issue_b_one = [&](int i) {
+        load16_to_lds((FUSED_UP && i >= LOADS / 2) ? b_ptr1 : b_ptr0, b_voff[i],
+                      smem + B_BASE + b_iss * B_BYTES + wave * 1024 + i * 8192);
+    };
     auto advance_a = [&]() {
-        ka += BK;
+        a_ptr += BK * 2;
         a_iss ^= 1;
     };
     // the weight K offset jumps at K segment ends (a step never straddles one)
     auto advance_b = [&]() {
-        kb += BK;
+        int64_t step_bytes = BK * 2;
         kpos += BK;
-        if (kpos == g.kseg_len) { kpos = 0; kb += g.kseg_stride - g.kseg_len; }
+        if (kpos == g.kseg_len) { kpos = 0; step_bytes += (g.kseg_stride - g.kseg_len) * 2; }
+        b_ptr0 += step_bytes;
+        b_ptr1 += step_bytes;
         b_iss = (b_iss + 1 == NBUF_B) ? 0 : b_iss + 1;
     };
     auto issue_a = [&]() {
@@ -312,13 +328,13 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     constexpr int BNW = SH::BNW, ROWB = SH::ROWB;
     constexpr int CH = ROWB / 16;               // 16-byte chunks per staged row
     constexpr int KSH = (ROWB == 128) ? 1 : 2;  // rows per 256 bytes of LDS = 1 << KSH
-    const int fhalf8 = fhalf * 8;
     // byte o of the wavefront's logical 4 KB staging area -> offset inside a weight buffer
     auto stg_off = [&](int o) { return wave * 1024 + (o >> 10) * 8192 + (o & 1023); };
     auto epilogue = [&](f32x16_t (&acc)[4][2], const Tile &t, int n0, int n_valid) {
         uint16_t *out = (uint16_t *)g.out;
         constexpr int ROWS_PER_IT = 64 / CH;
-        const int rr = lane / CH, cc = lane % CH;
+        const int el = opaque_lane(), frow = el & 31, fhalf8 = (el >> 5) * 8;  // not kept across the K loop
+        const int rr = el / CH, cc = el % CH;
         const int ncol = n0 + wn * BNW + cc * 8;
         const int wkey = (frow >> KSH) & (CH - 1);
         char *stg = smem + B_BASE + b_iss * B_BYTES;  // the buffer read in the tile's last step
