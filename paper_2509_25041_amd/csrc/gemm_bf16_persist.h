@@ -81,7 +81,8 @@ __device__ __forceinline__ int swizzle_key(int row) { return (row >> 1) & (CPR -
 // (the instruction the compiler's own builtin emits, LDS address in M0): the compiler then does
 // not count the load against the LDS counter, and the fragment reads around it keep their exact
 // per-read waits instead of "wait for everything".  The waits for these loads are explicit
-// s_waitcnt vmcnt(N) in the K loop.
+// s_waitcnt vmcnt(N) in the K loop.  M0 is written here only: nothing else in these kernels
+// needs it (LDS instructions do not on this target).
 __device__ __forceinline__ void load16_to_lds(const char *base, uint32_t voff, char *lds_wave_base) {
     const uint32_t lds_addr = (uint32_t)(size_t)(__attribute__((address_space(3))) char *)lds_wave_base;
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0" ::"s"(base), "v"(voff), "s"(lds_addr) : "memory");

@@ -367,6 +367,27 @@ def test_many_tiles_per_workgroup_element_by_element():
     assert not host(y)[:lo].any() and not host(y)[hi:].any()      # rows of the other rank untouched
 
 
+def test_more_than_64_local_slots_element_by_element():
+    """A rank hosting more than 64 expert instances (four row segments per lane in the GEMM's
+    segment table), many of them empty or a few rows long."""
+    cfg = LayerConfig("bf16_many_slots", T=1500, E=180, k=4, d=128, f=192, dtype="bf16", zipf_s=1.0, nodes=1,
+                      gpus_per_node=2, n_hot=4, replica_mode="all", seed=22)
+    wl = make_workload(cfg)
+    pl = wl.placement
+    lr = 1
+    ref = oracle.route_permute(wl.logits, pl, cfg.k, lr)
+    table, g = run_route_permute(wl, pl, cfg.k, lr)
+    check_route_permute(g, ref, wl, cfg.k)
+    experts = table.local_experts(lr)
+    assert len(experts) > 64
+    lo, hi = int(ref.perm.rank_off[lr]), int(ref.perm.rank_off[lr + 1])
+    wg, wu, wd = _stack_dev(wl, experts)
+    y = grace.grace_expert_ffn(table, lr, g.xp, g.ioff, cfg.T, cfg.k, wg, wu, wd)
+    torch.cuda.synchronize()
+    want = oracle.expert_ffn(ref, oracle.widen(wl.x), cfg.k, [lr], _weights64(wl), threads=8)
+    assert rel_err(oracle.widen(host(y))[lo:hi], want[lo:hi]) <= TOL["bf16"]
+
+
 def test_layer_object_rank_share_matches_oracle():
     cfg = SMALL["bf16_small"]
     wl = make_workload(cfg)
