@@ -33,7 +33,10 @@ const char *last_error();
 constexpr int WAVE = 64;
 
 // Assignments are ranked in chunks; one wavefront owns one chunk.
-constexpr int ROUTE_TOKENS_PER_CHUNK = 32;   // route: chunk = 32 tokens = 32*k assignments
+// route: chunk = 16 tokens (small batches: more workgroups) or 32 tokens (large batches: fewer
+// histogram rows to scan); the workspace is sized for the smaller one
+constexpr int ROUTE_CHUNK_SMALL = 16, ROUTE_CHUNK_LARGE = 32, ROUTE_SMALL_CHUNK_MAX_T = 8192;
+inline int route_chunk_tokens(int T) { return T <= ROUTE_SMALL_CHUNK_MAX_T ? ROUTE_CHUNK_SMALL : ROUTE_CHUNK_LARGE; }
 constexpr int PERM_CHUNK = 512;              // permute: chunk = 512 assignments
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

@@ -20,12 +20,11 @@
 
 namespace grace {
 
-constexpr int TOPK_THREADS = 512;                                   // 8 wavefronts per chunk
-constexpr int TOPK_TOK_PER_WAVE = ROUTE_TOKENS_PER_CHUNK / (TOPK_THREADS / 64);
+constexpr int TOPK_THREADS = 512;  // 8 wavefronts per chunk, TPW tokens each (chunk = 8 * TPW tokens)
 
 // One wavefront per token, VPL experts per lane (token_topk); a histogram of the chosen experts per
 // chunk of tokens feeds the request counter.
-template <int VPL>
+template <int VPL, int TOPK_TOK_PER_WAVE>
 __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *__restrict__ logits, int T, int E, int k,
                                                             int renorm, int32_t *__restrict__ topk_expert,
                                                             float *__restrict__ topk_weight,
@@ -35,7 +34,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *__restr
     for (int i = tid; i < E; i += TOPK_THREADS) hist[i] = 0;
     __syncthreads();
     const int chunk = (int)blockIdx.x;
-    const int t_begin = chunk * ROUTE_TOKENS_PER_CHUNK + wave * TOPK_TOK_PER_WAVE;
+    const int t_begin = (chunk * (TOPK_THREADS / 64) + wave) * TOPK_TOK_PER_WAVE;
     // all of this wavefront's logits are requested before any is used
     float raw[TOPK_TOK_PER_WAVE][VPL];
 #pragma unroll
@@ -103,7 +102,8 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
                                                             const int32_t *__restrict__ cand_ptr,
                                                             const int32_t *__restrict__ cand_g,
                                                             const uint32_t *__restrict__ cand_cum,
-                                                            int32_t *__restrict__ topk_inst, int nbits) {
+                                                            int32_t *__restrict__ topk_inst, int nbits,
+                                                            int chunk_tokens) {
     __shared__ uint32_t cnt[GRACE_MAX_EXPERTS];
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int chunk = (int)blockIdx.x;
@@ -132,8 +132,8 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
     if (wave != 0) return;
     // One wavefront walks the chunk in order.  Its LDS operations execute in program order, so a
     // counter updated by the last lane of a match set is seen by the next group of 64 assignments.
-    const int64_t a0 = (int64_t)chunk * ROUTE_TOKENS_PER_CHUNK * k;
-    const int64_t a1 = min(n_assign, a0 + (int64_t)ROUTE_TOKENS_PER_CHUNK * k);
+    const int64_t a0 = (int64_t)chunk * chunk_tokens * k;
+    const int64_t a1 = min(n_assign, a0 + (int64_t)chunk_tokens * k);
     const uint64_t lt = lanemask_lt();
     for (int64_t b = a0; b < a1; b += 64) {
         const int64_t a = b + lane;
@@ -158,16 +158,25 @@ inline bool fold_route_scan(int nchunks, int E) { return nchunks >= 1 && (int64_
 
 namespace grace {
 
-// Top-k gate of T >= 1 tokens; chunk_hist receives ceil(T / 32) x E expert counts.
+// Top-k gate of T >= 1 tokens; chunk_hist receives ceil(T / route_chunk_tokens(T)) x E expert counts.
 int launch_topk(const float *logits, int T, int E, int k, int renorm, int32_t *topk_expert, float *topk_weight,
                 int32_t *chunk_hist, hipStream_t st) {
-    const int nchunks = (int)ceil_div(T, ROUTE_TOKENS_PER_CHUNK);
+    const int chunk_tokens = route_chunk_tokens(T);
+    const int nchunks = (int)ceil_div(T, chunk_tokens);
+#define GRACE_TOPK(VPL)                                                                                              \
+    if (chunk_tokens == ROUTE_CHUNK_SMALL)                                                                           \
+        topk_kernel<VPL, ROUTE_CHUNK_SMALL / (TOPK_THREADS / 64)><<<nchunks, TOPK_THREADS, 0, st>>>(                \
+            logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist);                                          \
+    else                                                                                                             \
+        topk_kernel<VPL, ROUTE_CHUNK_LARGE / (TOPK_THREADS / 64)><<<nchunks, TOPK_THREADS, 0, st>>>(                \
+            logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist)
     switch ((E + 63) / 64) {
-        case 1: topk_kernel<1><<<nchunks, TOPK_THREADS, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist); break;
-        case 2: topk_kernel<2><<<nchunks, TOPK_THREADS, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist); break;
-        case 3: topk_kernel<3><<<nchunks, TOPK_THREADS, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist); break;
-        default: topk_kernel<4><<<nchunks, TOPK_THREADS, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist); break;
+        case 1: GRACE_TOPK(1); break;
+        case 2: GRACE_TOPK(2); break;
+        case 3: GRACE_TOPK(3); break;
+        default: GRACE_TOPK(4); break;
     }
+#undef GRACE_TOPK
     GRACE_LAUNCH_CHECK("topk_kernel");
     return GRACE_OK;
 }
@@ -204,7 +213,8 @@ extern "C" int grace_route(const grace_table *table, int32_t local_rank, grace_p
                                     topk_inst, expert_count, ws);
     if (rc != GRACE_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
-    const int nchunks = (int)ceil_div(T, ROUTE_TOKENS_PER_CHUNK);
+    const int chunk_tokens = route_chunk_tokens(T);
+    const int nchunks = (int)ceil_div(T, chunk_tokens);
     int32_t *hist = (int32_t *)ws;
     int32_t *base = (int32_t *)((char *)ws + align_up((size_t)nchunks * E * 4, 256));
     const int32_t *cand_ptr = table->d_cand_ptr + (size_t)(policy == GRACE_POLICY_WRR ? table->R : local_rank) * E;
@@ -217,7 +227,7 @@ extern "C" int grace_route(const grace_table *table, int32_t local_rank, grace_p
     if (fold_route_scan(nchunks, E)) {
         pick_kernel<true><<<nchunks, PICK_THREADS, 0, st>>>(topk_expert, (int64_t)T * k, E, k, hist, nchunks, rr_in, rr_out,
                                                   expert_count, cand_ptr, table->d_cand_g, table->d_cand_cum, topk_inst,
-                                                  nbits);
+                                                  nbits, chunk_tokens);
         GRACE_LAUNCH_CHECK("pick_kernel");
         return GRACE_OK;
     }
@@ -227,7 +237,7 @@ extern "C" int grace_route(const grace_table *table, int32_t local_rank, grace_p
     if (nchunks > 0) {
         pick_kernel<false><<<nchunks, PICK_THREADS, 0, st>>>(topk_expert, (int64_t)T * k, E, k, base, nchunks, rr_in, rr_out,
                                                    expert_count, cand_ptr, table->d_cand_g, table->d_cand_cum, topk_inst,
-                                                   nbits);
+                                                   nbits, chunk_tokens);
         GRACE_LAUNCH_CHECK("pick_kernel");
     }
     return GRACE_OK;

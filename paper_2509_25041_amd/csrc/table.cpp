@@ -229,7 +229,7 @@ extern "C" size_t grace_workspace_bytes(int32_t T, int32_t E, int32_t k, int32_t
     if (dt != GRACE_F32 && dt != GRACE_BF16) return 0;
     const size_t el = dt == GRACE_F32 ? 4 : 2;
     const size_t n = (size_t)T * (size_t)k;
-    const size_t chunks_r = (size_t)grace::ceil_div(T, grace::ROUTE_TOKENS_PER_CHUNK);
+    const size_t chunks_r = (size_t)grace::ceil_div(T, grace::ROUTE_CHUNK_SMALL);
     const size_t chunks_p = (size_t)grace::ceil_div((int64_t)n, grace::PERM_CHUNK);
     size_t need = 2 * grace::align_up(chunks_r * (size_t)E * 4, 256);
     need = std::max(need, 2 * grace::align_up(chunks_p * (size_t)I * 4, 256));
