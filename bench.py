@@ -89,6 +89,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="olmoe", help="olmoe (BASELINE configs[1], default) | qwen | dsv2lite | mixtral | tiny | olmoe_decode64 | olmoe_decode512")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rotate", type=int, default=1,
+                    help="also time the step cycling over this many independent sets of weights, inputs and buffers "
+                         "(cold Infinity Cache; for working sets below its 256 MB)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy kernel (known traffic, for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -140,21 +143,31 @@ def main() -> int:
     _, _, rank_ptr = table.instances()
     seg = np.diff(ioff[rank_ptr[lr]:rank_ptr[lr + 1] + 1])
 
-    # timed region: exactly `steps` steps, HIP events around every library call
-    # on the stream the kernels run on
+    # timed region: exactly `steps` steps; a pair of HIP events around the call that launches the
+    # dominant kernel, on the stream the kernels run on (every event is a marker packet between
+    # two kernels, so the other calls are timed in a second, untimed pass below)
     events = []
-    pool = [torch.cuda.Event(enable_timing=True) for _ in range(12 * args.steps)]
+    pool = [torch.cuda.Event(enable_timing=True) for _ in range(14 * args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        layer.forward(logits, x, events=events, event_pool=pool)
+        layer.forward(logits, x, events=events, event_pool=pool, timed_stages=("ffn_up",))
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
+    up_ms = float(np.mean([a.elapsed_time(b) for _, a, b in events]))
+
+    # every call's time: the same steps again with events around all of them
+    events = []
+    for _ in range(args.steps):
+        layer.forward(logits, x, events=events, event_pool=pool)
+    torch.cuda.synchronize()
     per_stage = {}
     for name, a, b in events:
         per_stage.setdefault(name, []).append(a.elapsed_time(b))
     stage_ms = {k: float(np.mean(v)) for k, v in per_stage.items()}
+    stage_ms["ffn_up_all_calls_timed"] = stage_ms["ffn_up"]
+    stage_ms["ffn_up"] = up_ms
 
     # the same step as one HIP graph launch (extra information; `value` stays the eager loop)
     graph = layer.capture(logits, x)
@@ -166,6 +179,26 @@ def main() -> int:
         graph.replay()
     torch.cuda.synchronize()
     graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # the same step cycling over several independent copies of everything it touches, so that no
+    # step finds its weights or buffers in the Infinity Cache
+    rotated_ms = None
+    if args.rotate > 1:
+        sets = [(layer, logits, x)]
+        for _ in range(args.rotate - 1):
+            shc = None if shd is None else tuple(w.clone() for w in shd)
+            sets.append((grace.GraceMoELayer(table, lr, cfg.T, cfg.k, cfg.d, cfg.f, tdt, wg.clone(), wu.clone(), wd.clone(),
+                                             shared=shc), logits.clone(), x.clone()))
+        for i in range(2 * len(sets)):
+            L, lg, xx = sets[i % len(sets)]
+            L.forward(lg, xx)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            L, lg, xx = sets[i % len(sets)]
+            L.forward(lg, xx)
+        torch.cuda.synchronize()
+        rotated_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
     d, f, k, T = cfg.d, cfg.f, cfg.k, cfg.T
     el = 4 if cfg.dtype == "f32" else 2
@@ -206,6 +239,8 @@ def main() -> int:
                      "traffic": traffic, "avg_launch_ms": stage_ms["ffn_up"]},
         "stages_ms": stage_ms,
         "graph_replay_ms_per_step": graph_ms,
+        "rotated_ms_per_step": rotated_ms,
+        "rotate_sets": args.rotate,
         "stages_achieved": {
             "ffn_down_TFLOPs": flops_down / (stage_ms["ffn_down"] * 1e-3) / 1e12,
             "combine_GBs": bytes_combine / (stage_ms["combine"] * 1e-3) / 1e9,

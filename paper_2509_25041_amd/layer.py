@@ -107,10 +107,12 @@ class GraceMoELayer:
     def forward(self, logits: torch.Tensor, x: torch.Tensor, rr_in: Optional[torch.Tensor] = None,
                 rr_out: Optional[torch.Tensor] = None,
                 events: Optional[List[Tuple[str, torch.cuda.Event, torch.cuda.Event]]] = None,
-                event_pool: Optional[List[torch.cuda.Event]] = None) -> torch.Tensor:
+                event_pool: Optional[List[torch.cuda.Event]] = None,
+                timed_stages: Optional[Tuple[str, ...]] = None) -> torch.Tensor:
         """One layer step on torch's current stream.  With `events` (a list to
-        append to), a pair of HIP events is recorded around every library call;
-        `event_pool` supplies pre-created timing events (popped two per call)."""
+        append to), a pair of HIP events is recorded around every library call,
+        or only around the calls named in `timed_stages`; `event_pool` supplies
+        pre-created timing events (popped two per timed call)."""
         stream = torch.cuda.current_stream().cuda_stream
         key = (logits.data_ptr(), x.data_ptr(), None if rr_in is None else rr_in.data_ptr(),
                None if rr_out is None else rr_out.data_ptr(), stream)
@@ -125,6 +127,11 @@ class GraceMoELayer:
                     _check(rc)
         else:
             for name, fn, args in self._calls:
+                if timed_stages is not None and name not in timed_stages:
+                    rc = fn(*args)
+                    if rc != 0:
+                        _check(rc)
+                    continue
                 if event_pool:
                     a, b = event_pool.pop(), event_pool.pop()
                 else:
