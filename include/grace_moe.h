@@ -165,10 +165,14 @@ int grace_permute(const grace_table *table, const int32_t *topk_inst, int32_t T,
 /* ---- grace_route_permute: grace_route then grace_permute in one call ----------
  * Same arguments, outputs (bit for bit) and errors as grace_route (Section 3,
  * Section 4.3, Algorithms 3 and 4) followed by grace_permute (Section 5) on its
- * topk_inst.  Decode-sized batches, which are bound by launch latency, are
- * handled by one single-workgroup kernel plus the row scatter instead of five
- * launches: that path is taken when ceil(T / 16) * k <= 256, E <= 256 and the
- * table has at most 256 instances; every other size runs the two calls.
+ * topk_inst, with fewer kernel launches.  Decode-sized batches, which are bound
+ * by launch latency, are handled by the top-k kernel, one single-workgroup
+ * kernel and the row scatter instead of five launches: that path is taken when
+ * ceil(T / 16) * k <= 256, E <= 256 and the table has at most 256 instances.
+ * For every other size the replica pick also produces the histograms the
+ * permutation starts from, which saves one launch.  The workspace holds the
+ * routing and the permutation histograms side by side during this call
+ * (grace_workspace_bytes covers it).
  */
 int grace_route_permute(const grace_table *table, int32_t local_rank, grace_policy policy, const float *logits, int32_t T,
                         int32_t E, int32_t k, int32_t renorm, const uint32_t *rr_in, uint32_t *rr_out,

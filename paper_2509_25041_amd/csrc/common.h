@@ -57,7 +57,14 @@ int check_permute_args(const grace_table *table, const int32_t *topk_inst, int32
                        grace_dtype dt, const int32_t *perm_pos, const int32_t *perm_src, const int32_t *inst_off,
                        const int32_t *rank_off, const int32_t *node_off, const void *xp, const void *ws);
 int launch_topk(const float *logits, int T, int E, int k, int renorm, int32_t *topk_expert, float *topk_weight,
-                int32_t *chunk_hist, hipStream_t st);
+                int32_t *chunk_hist, int32_t *clear, int n_clear, hipStream_t st);
+int launch_route(const grace_table *table, int32_t local_rank, grace_policy policy, const float *logits, int32_t T,
+                 int32_t E, int32_t k, int32_t renorm, const uint32_t *rr_in, uint32_t *rr_out, int32_t *topk_expert,
+                 float *topk_weight, int32_t *topk_inst, int32_t *expert_count, void *ws, int32_t *inst_hist,
+                 hipStream_t st);
+// Byte offset, inside the workspace, of the permutation's histograms when routing and permutation
+// share one call (the routing histograms of the same call lie below it).
+size_t fused_perm_ws_offset(int32_t T, int32_t E);
 int launch_scatter_rows(const void *x, int T, int k, int d, grace_dtype dt, const int32_t *perm_pos, void *xp,
                         hipStream_t st);
 

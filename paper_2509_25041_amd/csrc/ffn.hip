@@ -10,6 +10,8 @@
 // device; there is no host synchronisation).  The bf16 kernel is persistent (one
 // workgroup per compute unit walks the tiles); the fallback kernels size their
 // grid from an upper bound of the tile count and surplus blocks exit at once.
+#include <mutex>
+
 #include "bf16.h"
 #include "common.h"
 #include "gemm_bf16_generic.h"
@@ -32,6 +34,36 @@ static int compute_units() {
     return cached[dev];
 }
 
+// The persistent kernel needs the 160 KB of dynamic LDS opted in, once per kernel and device.
+static bool allow_full_lds(const void *kernel, const char *what) {
+    constexpr int MAX_KERNELS = 4, MAX_DEVICES = 64;
+    static std::mutex mu;
+    static const void *known[MAX_KERNELS] = {nullptr};
+    static bool done[MAX_KERNELS][MAX_DEVICES] = {{false}};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        fail(GRACE_EHIP, "%s: cannot query the device", what);
+        return false;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    int slot = 0;
+    while (slot < MAX_KERNELS && known[slot] && known[slot] != kernel) ++slot;
+    if (slot == MAX_KERNELS) {
+        fail(GRACE_EHIP, "%s: kernel table full", what);
+        return false;
+    }
+    known[slot] = kernel;
+    if (!done[slot][dev]) {
+        const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, pers::LDS_BYTES);
+        if (e != hipSuccess) {
+            fail(GRACE_EHIP, "%s: cannot reserve LDS: %s", what, hipGetErrorString(e));
+            return false;
+        }
+        done[slot][dev] = true;
+    }
+    return true;
+}
+
 template <bool FUSED_UP>
 static int launch_gemm(const GemmArgs &g, grace_dtype dt, int64_t m_bound, hipStream_t st, const char *what) {
     if (m_bound <= 0 || g.N <= 0 || g.K <= 0) return GRACE_OK;
@@ -46,14 +78,10 @@ static int launch_gemm(const GemmArgs &g, grace_dtype dt, int64_t m_bound, hipSt
         const int ntn = (g.N + SH::BN - 1) / SH::BN;
         const int grid = pers::grid_blocks(n_cu);
         if (n_seg <= 64) {
-            static const hipError_t attr = hipFuncSetAttribute((const void *)pers::gemm_bf16_persist_kernel<FUSED_UP, 1>,
-                                                               hipFuncAttributeMaxDynamicSharedMemorySize, pers::LDS_BYTES);
-            if (attr != hipSuccess) return fail(GRACE_EHIP, "%s: cannot reserve LDS: %s", what, hipGetErrorString(attr));
+            if (!allow_full_lds((const void *)pers::gemm_bf16_persist_kernel<FUSED_UP, 1>, what)) return GRACE_EHIP;
             pers::gemm_bf16_persist_kernel<FUSED_UP, 1><<<grid, pers::THREADS, pers::LDS_BYTES, st>>>(g, ntn);
         } else {
-            static const hipError_t attr = hipFuncSetAttribute((const void *)pers::gemm_bf16_persist_kernel<FUSED_UP, 4>,
-                                                               hipFuncAttributeMaxDynamicSharedMemorySize, pers::LDS_BYTES);
-            if (attr != hipSuccess) return fail(GRACE_EHIP, "%s: cannot reserve LDS: %s", what, hipGetErrorString(attr));
+            if (!allow_full_lds((const void *)pers::gemm_bf16_persist_kernel<FUSED_UP, 4>, what)) return GRACE_EHIP;
             pers::gemm_bf16_persist_kernel<FUSED_UP, 4><<<grid, pers::THREADS, pers::LDS_BYTES, st>>>(g, ntn);
         }
     } else if (dt == GRACE_BF16) {

@@ -28,10 +28,13 @@ template <int VPL, int TOPK_TOK_PER_WAVE>
 __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *__restrict__ logits, int T, int E, int k,
                                                             int renorm, int32_t *__restrict__ topk_expert,
                                                             float *__restrict__ topk_weight,
-                                                            int32_t *__restrict__ chunk_hist) {
+                                                            int32_t *__restrict__ chunk_hist,
+                                                            int32_t *__restrict__ clear, int n_clear) {
     __shared__ int32_t hist[GRACE_MAX_EXPERTS];
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (int i = tid; i < E; i += TOPK_THREADS) hist[i] = 0;
+    // counters a later kernel of the same call accumulates into
+    for (int i = (int)blockIdx.x * TOPK_THREADS + tid; i < n_clear; i += (int)gridDim.x * TOPK_THREADS) clear[i] = 0;
     __syncthreads();
     const int chunk = (int)blockIdx.x;
     const int t_begin = (chunk * (TOPK_THREADS / 64) + wave) * TOPK_TOK_PER_WAVE;
@@ -91,6 +94,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void route_scan_kernel(const int32_t 
 // FOLD = false: chunk_counts is the scanned histogram (requests of each expert before each chunk).
 // FOLD = true: chunk_counts is the raw per-chunk histogram; the block sums the rows before its own,
 // and the last block also writes expert_count and rr_out.
+// With inst_hist (zeroed beforehand) every pick is also counted per chunk of PERM_CHUNK assignments
+// and instance: the histogram the dispatch permutation starts from (integer atomics: exact in any order).
 constexpr int PICK_THREADS = 256;  // wavefront 0 ranks; all four sum histogram rows when FOLD
 
 template <bool FOLD>
@@ -103,7 +108,7 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
                                                             const int32_t *__restrict__ cand_g,
                                                             const uint32_t *__restrict__ cand_cum,
                                                             int32_t *__restrict__ topk_inst, int nbits,
-                                                            int chunk_tokens) {
+                                                            int chunk_tokens, int32_t *__restrict__ inst_hist, int I) {
     __shared__ uint32_t cnt[GRACE_MAX_EXPERTS];
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int chunk = (int)blockIdx.x;
@@ -144,7 +149,9 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
         if (valid) {
             const uint32_t rank = (uint32_t)__popcll(same & lt);
             const uint64_t c = (uint64_t)cnt[e] + rank + (uint64_t)(rr_in ? rr_in[e] : 0u);
-            topk_inst[a] = pick_candidate(c, e, cand_ptr, cand_g, cand_cum);
+            const int g = pick_candidate(c, e, cand_ptr, cand_g, cand_cum);
+            topk_inst[a] = g;
+            if (inst_hist && (unsigned)g < (unsigned)I) atomicAdd(&inst_hist[(a / PERM_CHUNK) * I + g], 1);
         }
         if (valid && is_last_of(same)) cnt[e] += (uint32_t)__popcll(same);
     }
@@ -160,16 +167,16 @@ namespace grace {
 
 // Top-k gate of T >= 1 tokens; chunk_hist receives ceil(T / route_chunk_tokens(T)) x E expert counts.
 int launch_topk(const float *logits, int T, int E, int k, int renorm, int32_t *topk_expert, float *topk_weight,
-                int32_t *chunk_hist, hipStream_t st) {
+                int32_t *chunk_hist, int32_t *clear, int n_clear, hipStream_t st) {
     const int chunk_tokens = route_chunk_tokens(T);
     const int nchunks = (int)ceil_div(T, chunk_tokens);
 #define GRACE_TOPK(VPL)                                                                                              \
     if (chunk_tokens == ROUTE_CHUNK_SMALL)                                                                           \
         topk_kernel<VPL, ROUTE_CHUNK_SMALL / (TOPK_THREADS / 64)><<<nchunks, TOPK_THREADS, 0, st>>>(                \
-            logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist);                                          \
+            logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist, clear, n_clear);                          \
     else                                                                                                             \
         topk_kernel<VPL, ROUTE_CHUNK_LARGE / (TOPK_THREADS / 64)><<<nchunks, TOPK_THREADS, 0, st>>>(                \
-            logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist)
+            logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist, clear, n_clear)
     switch ((E + 63) / 64) {
         case 1: GRACE_TOPK(1); break;
         case 2: GRACE_TOPK(2); break;
@@ -204,22 +211,23 @@ int check_route_args(const grace_table *table, int32_t local_rank, grace_policy 
 
 }  // namespace grace
 
-using namespace grace;
+namespace grace {
 
-extern "C" int grace_route(const grace_table *table, int32_t local_rank, grace_policy policy, const float *logits, int32_t T, int32_t E,
-                           int32_t k, int32_t renorm, const uint32_t *rr_in, uint32_t *rr_out, int32_t *topk_expert,
-                           float *topk_weight, int32_t *topk_inst, int32_t *expert_count, void *ws, void *stream) {
-    const int rc = check_route_args(table, local_rank, policy, logits, T, E, k, rr_in, rr_out, topk_expert, topk_weight,
-                                    topk_inst, expert_count, ws);
-    if (rc != GRACE_OK) return rc;
-    hipStream_t st = (hipStream_t)stream;
+// The launches of grace_route for T >= 0 checked arguments.  With inst_hist (ceil(T*k / PERM_CHUNK) x I
+// counters, T >= 1) the picks are also counted per permutation chunk and instance.
+int launch_route(const grace_table *table, int32_t local_rank, grace_policy policy, const float *logits, int32_t T,
+                 int32_t E, int32_t k, int32_t renorm, const uint32_t *rr_in, uint32_t *rr_out, int32_t *topk_expert,
+                 float *topk_weight, int32_t *topk_inst, int32_t *expert_count, void *ws, int32_t *inst_hist,
+                 hipStream_t st) {
     const int chunk_tokens = route_chunk_tokens(T);
     const int nchunks = (int)ceil_div(T, chunk_tokens);
+    const int I = table->I;
     int32_t *hist = (int32_t *)ws;
     int32_t *base = (int32_t *)((char *)ws + align_up((size_t)nchunks * E * 4, 256));
     const int32_t *cand_ptr = table->d_cand_ptr + (size_t)(policy == GRACE_POLICY_WRR ? table->R : local_rank) * E;
     if (nchunks > 0) {
-        const int rc_topk = launch_topk(logits, T, E, k, renorm, topk_expert, topk_weight, hist, st);
+        const int64_t n_clear = inst_hist ? ceil_div((int64_t)T * k, PERM_CHUNK) * I : 0;
+        const int rc_topk = launch_topk(logits, T, E, k, renorm, topk_expert, topk_weight, hist, inst_hist, (int)n_clear, st);
         if (rc_topk != GRACE_OK) return rc_topk;
     }
     int nbits = 0;
@@ -227,7 +235,7 @@ extern "C" int grace_route(const grace_table *table, int32_t local_rank, grace_p
     if (fold_route_scan(nchunks, E)) {
         pick_kernel<true><<<nchunks, PICK_THREADS, 0, st>>>(topk_expert, (int64_t)T * k, E, k, hist, nchunks, rr_in, rr_out,
                                                   expert_count, cand_ptr, table->d_cand_g, table->d_cand_cum, topk_inst,
-                                                  nbits, chunk_tokens);
+                                                  nbits, chunk_tokens, inst_hist, I);
         GRACE_LAUNCH_CHECK("pick_kernel");
         return GRACE_OK;
     }
@@ -237,8 +245,22 @@ extern "C" int grace_route(const grace_table *table, int32_t local_rank, grace_p
     if (nchunks > 0) {
         pick_kernel<false><<<nchunks, PICK_THREADS, 0, st>>>(topk_expert, (int64_t)T * k, E, k, base, nchunks, rr_in, rr_out,
                                                    expert_count, cand_ptr, table->d_cand_g, table->d_cand_cum, topk_inst,
-                                                   nbits, chunk_tokens);
+                                                   nbits, chunk_tokens, inst_hist, I);
         GRACE_LAUNCH_CHECK("pick_kernel");
     }
     return GRACE_OK;
+}
+
+}  // namespace grace
+
+using namespace grace;
+
+extern "C" int grace_route(const grace_table *table, int32_t local_rank, grace_policy policy, const float *logits, int32_t T, int32_t E,
+                           int32_t k, int32_t renorm, const uint32_t *rr_in, uint32_t *rr_out, int32_t *topk_expert,
+                           float *topk_weight, int32_t *topk_inst, int32_t *expert_count, void *ws, void *stream) {
+    const int rc = check_route_args(table, local_rank, policy, logits, T, E, k, rr_in, rr_out, topk_expert, topk_weight,
+                                    topk_inst, expert_count, ws);
+    if (rc != GRACE_OK) return rc;
+    return launch_route(table, local_rank, policy, logits, T, E, k, renorm, rr_in, rr_out, topk_expert, topk_weight,
+                        topk_inst, expert_count, ws, nullptr, (hipStream_t)stream);
 }

@@ -1,5 +1,9 @@
 // grace_route_permute: grace_route followed by grace_permute as one call.
 //
+// Any batch: the replica pick also counts its choices per permutation chunk and
+// instance (into counters the top-k kernel cleared), so the permutation's own
+// histogram launch is dropped: top-k, pick, positions, row scatter.
+//
 // Decode-sized batches (a few hundred tokens) are bound by launch latency: the
 // two calls need five launches of kernels that each run a few microseconds.  When
 // the batch is small enough, the top-k gate (one wavefront per token, spread over
@@ -9,10 +13,11 @@
 //   2. replica pick        Algorithm 4 tier + weighted round-robin, per wavefront in order
 //   3. offsets             per instance / rank / node, scan of the per-wavefront instance counts
 //   4. positions           stable rank of every assignment in (node, rank, slot) order (Section 5)
-// and by the row scatter: three launches.  Larger batches take the two-call path.
+// and by the row scatter: three launches.
 // Outputs are identical either way (all integer work is exact and order-independent).
 #include "common.h"
 #include "route_device.h"
+#include "stable_sort.h"
 #include "wave_utils.h"
 
 namespace grace {
@@ -167,16 +172,32 @@ extern "C" int grace_route_permute(const grace_table *table, int32_t local_rank,
     if (rc != GRACE_OK) return rc;
     rc = check_permute_args(table, topk_inst, T, k, x, d, dt, perm_pos, perm_src, inst_off, rank_off, node_off, xp, ws);
     if (rc != GRACE_OK) return rc;
-    if (!small_batch(T, k, E, table->I)) {
+    hipStream_t st = (hipStream_t)stream;
+    if (T == 0) {
         rc = grace_route(table, local_rank, policy, logits, T, E, k, renorm, rr_in, rr_out, topk_expert, topk_weight,
                          topk_inst, expert_count, ws, stream);
         if (rc != GRACE_OK) return rc;
         return grace_permute(table, topk_inst, T, k, x, d, dt, perm_pos, perm_src, inst_off, rank_off, node_off, xp, ws,
                              stream);
     }
-    hipStream_t st = (hipStream_t)stream;
+    if (!small_batch(T, k, E, table->I)) {
+        const int I = table->I;
+        const int64_t n = (int64_t)T * k;
+        const int nchunks = (int)ceil_div(n, PERM_CHUNK);
+        int32_t *phist = (int32_t *)((char *)ws + fused_perm_ws_offset(T, E));
+        int32_t *pbase = (int32_t *)((char *)phist + align_up((size_t)nchunks * I * 4, 256));
+        rc = launch_route(table, local_rank, policy, logits, T, E, k, renorm, rr_in, rr_out, topk_expert, topk_weight,
+                          topk_inst, expert_count, ws, phist, st);
+        if (rc != GRACE_OK) return rc;
+        const char *failed = stable_sort_launch(topk_inst, n, I, 1, phist, pbase, table->R, table->N, table->d_rank_ptr,
+                                                table->d_node_first_inst, inst_off, rank_off, node_off, perm_pos, perm_src,
+                                                st, /*hist_ready=*/true);
+        if (failed) return fail(GRACE_EHIP, "route_permute: launch of %s failed", failed);
+        if (x) return launch_scatter_rows(x, T, k, d, dt, perm_pos, xp, st);
+        return GRACE_OK;
+    }
     const int32_t *cand_ptr = table->d_cand_ptr + (size_t)(policy == GRACE_POLICY_WRR ? table->R : local_rank) * E;
-    rc = launch_topk(logits, T, E, k, renorm, topk_expert, topk_weight, (int32_t *)ws, st);
+    rc = launch_topk(logits, T, E, k, renorm, topk_expert, topk_weight, (int32_t *)ws, nullptr, 0, st);
     if (rc != GRACE_OK) return rc;
     dispatch_small_kernel<<<1, SMALL_THREADS, 0, st>>>(T, E, k, rr_in, rr_out, cand_ptr, table->d_cand_g, table->d_cand_cum,
                                                       table->I, table->R, table->N, table->d_rank_ptr,

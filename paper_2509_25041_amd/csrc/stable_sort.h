@@ -177,14 +177,16 @@ static __global__ __launch_bounds__(POS_FOLD_THREADS) void key_pos_fold_kernel(
 
 // Host side: the launches of one stable counting sort.  hist / base: workspace of nchunks * nkeys
 // ints each.  rank_ptr .. node_off may be null (plain sort: only `off` is produced).
+// hist_ready: an earlier kernel on the stream already wrote the chunk histograms into `hist`.
 static inline const char *stable_sort_launch(const int32_t *keys, int64_t n, int nkeys, int src_div, int32_t *hist,
                                              int32_t *base, int R, int N, const int32_t *rank_ptr,
                                              const int32_t *node_first_inst, int32_t *off, int32_t *rank_off,
-                                             int32_t *node_off, int32_t *pos, int32_t *src, hipStream_t st) {
+                                             int32_t *node_off, int32_t *pos, int32_t *src, hipStream_t st,
+                                             bool hist_ready = false) {
     const int nchunks = (int)ceil_div(n, PERM_CHUNK);
     int nbits = 0;
     while ((1 << nbits) < nkeys) ++nbits;
-    if (nchunks > 0) {
+    if (nchunks > 0 && !hist_ready) {
         key_hist_kernel<<<nchunks, 64, 0, st>>>(keys, n, nkeys, hist);
         if (hipGetLastError() != hipSuccess) return "key_hist_kernel";
     }

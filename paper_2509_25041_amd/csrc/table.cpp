@@ -223,16 +223,21 @@ extern "C" int grace_table_local_experts(const grace_table *t, int32_t rank, int
     return GRACE_OK;
 }
 
+namespace grace {
+size_t fused_perm_ws_offset(int32_t T, int32_t E) {
+    return 2 * align_up((size_t)ceil_div(T, ROUTE_CHUNK_SMALL) * (size_t)E * 4, 256);
+}
+}  // namespace grace
+
 extern "C" size_t grace_workspace_bytes(int32_t T, int32_t E, int32_t k, int32_t I, int32_t d, int32_t f,
                                         int32_t n_shared, grace_dtype dt) {
     if (T < 0 || E < 1 || k < 1 || I < 1 || d < 0 || f < 0 || n_shared < 0) return 0;
     if (dt != GRACE_F32 && dt != GRACE_BF16) return 0;
     const size_t el = dt == GRACE_F32 ? 4 : 2;
     const size_t n = (size_t)T * (size_t)k;
-    const size_t chunks_r = (size_t)grace::ceil_div(T, grace::ROUTE_CHUNK_SMALL);
     const size_t chunks_p = (size_t)grace::ceil_div((int64_t)n, grace::PERM_CHUNK);
-    size_t need = 2 * grace::align_up(chunks_r * (size_t)E * 4, 256);
-    need = std::max(need, 2 * grace::align_up(chunks_p * (size_t)I * 4, 256));
+    // routing and permutation histograms side by side (grace_route_permute uses both at once)
+    size_t need = grace::fused_perm_ws_offset(T, E) + 2 * grace::align_up(chunks_p * (size_t)I * 4, 256);
     need = std::max(need, grace::align_up(n * (size_t)f * el, 256));
     need = std::max(need, grace::align_up((size_t)T * (size_t)n_shared * (size_t)f * el, 256));
     // send lists: five int32 arrays over the assignments + chunk histograms over up to GRACE_MAX_RANKS keys

@@ -20,7 +20,7 @@ class GraceMoELayer:
     Rows of other ranks stay zero in `y` (their results would arrive over the
     reverse all-to-all in a multi-GPU deployment).
 
-    All buffers are allocated once; a step is six C calls whose argument lists
+    All buffers are allocated once; a step is four or five C calls whose argument lists
     are marshalled once per (logits, x, rr_in, rr_out, stream) and reused, so the
     host cost of a step is a few microseconds per call.
     """
@@ -57,8 +57,9 @@ class GraceMoELayer:
         self.dt = _dtype_code(self.xp)
         self.ws = torch.empty(grace_workspace_bytes(T, table.E, k, table.I, d, f, self.n_shared, self.dt),
                               dtype=torch.uint8, device=device)
-        # decode-sized batches: routing and permutation as one call (one single-workgroup kernel)
-        self.single_call_dispatch = (T >= 1 and table.E <= 256 and table.I <= 256 and -(-T // 16) * k <= 256)
+        # routing and permutation as one call (fewer launches than grace_route + grace_permute);
+        # False: the two separate calls
+        self.single_call_dispatch = True
         self._key = None
         self._calls: List[Tuple[str, object, tuple]] = []
 

@@ -102,6 +102,7 @@ def test_route_and_permute_many_chunks_separate_scan_kernels():
     ref = oracle.route_permute(wl.logits, wl.placement, cfg.k, 3)
     _, g = run_route_permute(wl, wl.placement, cfg.k, 3)
     check_route_permute(g, ref, wl, cfg.k)
+    check_route_permute(run_fused(wl, wl.placement, cfg.k, 3), ref, wl, cfg.k)   # the same as one call
 
 
 def test_route_rr_carry_and_no_renorm():
@@ -165,11 +166,12 @@ def run_fused(wl, pl, k, local_rank, rr_in=None, renorm=1, with_rows=True, polic
     ("tiny", None, 0), ("tiny", 1, 1), ("tiny", 15, 3), ("tiny", 17, 2), ("tiny", 2048, 0),   # 2048: single kernel at k=2
     ("olmoe_decode64", None, 0), ("olmoe_decode512", None, 0), ("olmoe", 100, 2), ("olmoe", 513, 1),
     ("qwen", 200, 5), ("dsv2lite", 300, 17), ("mixtral", 1000, 6),
-    ("olmoe", None, 0),                                                                   # two-call path
+    # larger batches: the pick kernel also fills the permutation's chunk histograms
+    ("olmoe", None, 0), ("qwen", 5001, 5), ("dsv2lite", None, 17), ("mixtral", None, 6), ("qwen3moe", 3000, 3),
 ])
 def test_route_permute_single_call_bit_exact(name, T, local_rank):
     """grace_route_permute gives the outputs of the two calls, on the single-workgroup path
-    (decode-sized batches) and on the chained path alike."""
+    (decode-sized batches) and on the path for larger batches alike."""
     cfg = CONFIGS[name]
     wl = make_workload(cfg, T=T)
     ref = oracle.route_permute(wl.logits, wl.placement, cfg.k, local_rank)
