@@ -96,7 +96,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void route_scan_kernel(const int32_t 
 // and the last block also writes expert_count and rr_out.
 // With inst_hist (zeroed beforehand) every pick is also counted per chunk of PERM_CHUNK assignments
 // and instance: the histogram the dispatch permutation starts from (integer atomics: exact in any order).
-constexpr int PICK_THREADS = 256;  // wavefront 0 ranks; all four sum histogram rows when FOLD
+constexpr int PICK_THREADS = 512;  // wavefront 0 ranks; all eight sum histogram rows when FOLD
 
 template <bool FOLD>
 __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__restrict__ topk_expert, int64_t n_assign,
@@ -116,11 +116,23 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
         // requests before this chunk: the wavefronts share the histogram rows 0 .. chunk-1
         for (int e = tid; e < E; e += PICK_THREADS) cnt[e] = 0;
         __syncthreads();
-        for (int e = lane; e < E; e += 64) {
-            int32_t part = 0;
+        constexpr int NW = PICK_THREADS / 64;
+        const int nkb = (E + 63) / 64;  // blocks of 64 experts; a wavefront stays on one when nkb divides NW
+        if (NW % nkb == 0) {
+            const int e = (wave % nkb) * 64 + lane, rstep = NW / nkb;
+            if (e < E) {
+                int32_t part = 0;
 #pragma unroll 8
-            for (int c = wave; c < chunk; c += PICK_THREADS / 64) part += chunk_counts[(size_t)c * E + e];
-            if (part) atomicAdd(&cnt[e], (uint32_t)part);  // integer sum: order does not matter
+                for (int c = wave / nkb; c < chunk; c += rstep) part += chunk_counts[(size_t)c * E + e];
+                if (part) atomicAdd(&cnt[e], (uint32_t)part);  // integer sum: order does not matter
+            }
+        } else {
+            for (int e = lane; e < E; e += 64) {
+                int32_t part = 0;
+#pragma unroll 8
+                for (int c = wave; c < chunk; c += NW) part += chunk_counts[(size_t)c * E + e];
+                if (part) atomicAdd(&cnt[e], (uint32_t)part);
+            }
         }
         __syncthreads();
         if (chunk == nchunks - 1) {

@@ -119,7 +119,7 @@ static __global__ __launch_bounds__(64) void key_pos_kernel(const int32_t *__res
 constexpr int FOLD_MAX_LOADS = 1024;  // histogram loads a block may spend per key column on its own scan
 inline bool fold_scan(int nchunks, int nkeys) { return nchunks >= 1 && (int64_t)nchunks * ((nkeys + 63) / 64) <= FOLD_MAX_LOADS; }
 
-constexpr int POS_FOLD_THREADS = 256;  // all four wavefronts sum histogram rows; wavefront 0 scans and ranks
+constexpr int POS_FOLD_THREADS = 512;  // all eight wavefronts sum histogram rows; wavefront 0 scans and ranks
 
 static __global__ __launch_bounds__(POS_FOLD_THREADS) void key_pos_fold_kernel(
     const int32_t *__restrict__ keys, int64_t n_items, int I, const int32_t *__restrict__ chunk_hist, int nchunks, int R,
@@ -135,16 +135,35 @@ static __global__ __launch_bounds__(POS_FOLD_THREADS) void key_pos_fold_kernel(
         off[i] = 0;
     }
     __syncthreads();
-    for (int key = lane; key < I; key += 64) {
-        int32_t tot = 0, prev = 0;
+    // (block of 64 keys, histogram row) pairs are dealt to the wavefronts; when the number of key
+    // blocks divides the number of wavefronts each wavefront stays on one key block
+    constexpr int NW = POS_FOLD_THREADS / 64;
+    const int nkb = (I + 63) / 64;
+    if (NW % nkb == 0) {
+        const int key = (wave % nkb) * 64 + lane, rstep = NW / nkb;
+        if (key < I) {
+            int32_t tot = 0, prev = 0;
 #pragma unroll 8
-        for (int c = wave; c < nchunks; c += POS_FOLD_THREADS / 64) {
-            const int32_t v = chunk_hist[(size_t)c * I + key];
-            tot += v;
-            prev += (c < chunk) ? v : 0;
+            for (int c = wave / nkb; c < nchunks; c += rstep) {
+                const int32_t v = chunk_hist[(size_t)c * I + key];
+                tot += v;
+                prev += (c < chunk) ? v : 0;
+            }
+            if (tot) atomicAdd(&off[key], tot);  // integer sums: order does not matter
+            if (prev) atomicAdd(&cnt[key], prev);
         }
-        if (tot) atomicAdd(&off[key], tot);  // integer sums: order does not matter
-        if (prev) atomicAdd(&cnt[key], prev);
+    } else {
+        for (int key = lane; key < I; key += 64) {
+            int32_t tot = 0, prev = 0;
+#pragma unroll 8
+            for (int c = wave; c < nchunks; c += NW) {
+                const int32_t v = chunk_hist[(size_t)c * I + key];
+                tot += v;
+                prev += (c < chunk) ? v : 0;
+            }
+            if (tot) atomicAdd(&off[key], tot);
+            if (prev) atomicAdd(&cnt[key], prev);
+        }
     }
     __syncthreads();
     if (wave != 0) return;
