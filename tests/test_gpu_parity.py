@@ -204,9 +204,12 @@ def test_route_permute_single_call_carry_policy_and_wide_experts():
     check_route_permute(g, ref, wl2, k)
 
 
-@pytest.mark.parametrize("E,k,T", [(128, 8, 1500), (200, 5, 700), (256, 64, 300), (8, 8, 100), (3, 1, 129)])
+@pytest.mark.parametrize("E,k,T", [(128, 8, 1500), (200, 5, 700), (256, 64, 300), (8, 8, 100), (3, 1, 129),
+                                   (64, 20, 300), (40, 40, 200), (100, 50, 150), (128, 64, 90)])
 def test_route_wide_and_degenerate_expert_counts(E, k, T):
-    """More than one expert per lane (E > 64), k = E, k = 1, ties everywhere."""
+    """More than one expert per lane (E > 64), k = E, k = 1, ties everywhere; small k takes the
+    arg-max rounds of the top-k kernel, the last four cases (large k for their E) its
+    rank-by-broadcast path."""
     rng = np.random.default_rng(E + k)
     R, N = 6, 3
     hosts = [sorted(rng.choice(R, size=rng.integers(1, 4), replace=False).tolist()) for _ in range(E)]
