@@ -96,6 +96,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void route_scan_kernel(const int32_t 
 // and the last block also writes expert_count and rr_out.
 // With inst_hist (zeroed beforehand) every pick is also counted per chunk of PERM_CHUNK assignments
 // and instance: the histogram the dispatch permutation starts from (integer atomics: exact in any order).
+constexpr int PICK_LDS_CANDS = 1024;  // candidate entries of one view that are staged in LDS (else read from global memory)
+constexpr int PICK_BATCH = 4;         // rounds of 64 assignments whose experts are fetched together
 constexpr int PICK_THREADS = 512;  // wavefront 0 ranks; all eight sum histogram rows when FOLD
 
 template <bool FOLD>
@@ -110,8 +112,33 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
                                                             int32_t *__restrict__ topk_inst, int nbits,
                                                             int chunk_tokens, int32_t *__restrict__ inst_hist, int I) {
     __shared__ uint32_t cnt[GRACE_MAX_EXPERTS];
+    __shared__ int32_t s_ptr[GRACE_MAX_EXPERTS + 1];  // this view's candidate lists, offsets from its first entry
+    __shared__ int32_t s_g[PICK_LDS_CANDS];
+    __shared__ uint32_t s_cum[PICK_LDS_CANDS];
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int chunk = (int)blockIdx.x;
+    const int64_t a0 = (int64_t)chunk * chunk_tokens * k;
+    const int64_t a1 = min(n_assign, a0 + (int64_t)chunk_tokens * k);
+    // the first rounds' experts and the candidate table are fetched before the counters are
+    // prepared, so the picks below do not wait on chains of dependent global loads
+    int e_in[PICK_BATCH];
+    auto load_batch = [&](int64_t b0) {
+#pragma unroll
+        for (int q = 0; q < PICK_BATCH; ++q) {
+            const int64_t a = b0 + q * 64 + lane;
+            e_in[q] = a < a1 ? topk_expert[a] : -1;
+        }
+    };
+    if (wave == 0) load_batch(a0);
+    const int c_first = cand_ptr[0], n_cand = cand_ptr[E] - c_first;
+    const bool table_in_lds = n_cand <= PICK_LDS_CANDS;  // uniform
+    if (table_in_lds) {
+        for (int i = tid; i <= E; i += PICK_THREADS) s_ptr[i] = cand_ptr[i] - c_first;
+        for (int i = tid; i < n_cand; i += PICK_THREADS) {
+            s_g[i] = cand_g[c_first + i];
+            s_cum[i] = cand_cum[c_first + i];
+        }
+    }
     if (FOLD) {
         // requests before this chunk: the wavefronts share the histogram rows 0 .. chunk-1
         for (int e = tid; e < E; e += PICK_THREADS) cnt[e] = 0;
@@ -149,23 +176,29 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
     if (wave != 0) return;
     // One wavefront walks the chunk in order.  Its LDS operations execute in program order, so a
     // counter updated by the last lane of a match set is seen by the next group of 64 assignments.
-    const int64_t a0 = (int64_t)chunk * chunk_tokens * k;
-    const int64_t a1 = min(n_assign, a0 + (int64_t)chunk_tokens * k);
+    const int32_t *t_ptr = table_in_lds ? s_ptr : cand_ptr;
+    const int32_t *t_g = table_in_lds ? s_g : cand_g;
+    const uint32_t *t_cum = table_in_lds ? s_cum : cand_cum;
     const uint64_t lt = lanemask_lt();
-    for (int64_t b = a0; b < a1; b += 64) {
-        const int64_t a = b + lane;
-        bool valid = a < a1;
-        int e = valid ? topk_expert[a] : 0;
-        valid = valid && (unsigned)e < (unsigned)E;
-        const uint64_t same = wave_match((uint32_t)e, valid, nbits);
-        if (valid) {
-            const uint32_t rank = (uint32_t)__popcll(same & lt);
-            const uint64_t c = (uint64_t)cnt[e] + rank + (uint64_t)(rr_in ? rr_in[e] : 0u);
-            const int g = pick_candidate(c, e, cand_ptr, cand_g, cand_cum);
-            topk_inst[a] = g;
-            if (inst_hist && (unsigned)g < (unsigned)I) atomicAdd(&inst_hist[(a / PERM_CHUNK) * I + g], 1);
+    for (int64_t b0 = a0; b0 < a1; b0 += PICK_BATCH * 64) {
+        if (b0 != a0) load_batch(b0);
+#pragma unroll
+        for (int q = 0; q < PICK_BATCH; ++q) {
+            if (b0 + q * 64 >= a1) break;  // uniform
+            const int64_t a = b0 + q * 64 + lane;
+            const int e_raw = e_in[q];
+            const bool valid = (unsigned)e_raw < (unsigned)E;  // -1 past the end of the chunk
+            const int e = valid ? e_raw : 0;
+            const uint64_t same = wave_match((uint32_t)e, valid, nbits);
+            if (valid) {
+                const uint32_t rank = (uint32_t)__popcll(same & lt);
+                const uint64_t c = (uint64_t)cnt[e] + rank + (uint64_t)(rr_in ? rr_in[e] : 0u);
+                const int g = pick_candidate(c, e, t_ptr, t_g, t_cum);
+                topk_inst[a] = g;
+                if (inst_hist && (unsigned)g < (unsigned)I) atomicAdd(&inst_hist[(a / PERM_CHUNK) * I + g], 1);
+            }
+            if (valid && is_last_of(same)) cnt[e] += (uint32_t)__popcll(same);
         }
-        if (valid && is_last_of(same)) cnt[e] += (uint32_t)__popcll(same);
     }
 }
 

@@ -76,16 +76,32 @@ static __global__ __launch_bounds__(SCAN_THREADS) void key_scan_kernel(const int
 // next item with that key; equal keys inside a group of 64 items are ranked by ballot matching.
 // The LDS operations of one wavefront execute in program order, so a counter updated by the last
 // lane of a match set is seen by the next group of 64 items without a barrier.
-__device__ __forceinline__ void rank_chunk(const int32_t *__restrict__ keys, int64_t n_items, int nkeys, int32_t *cnt,
+// The chunk's keys are fetched up front (load_chunk_keys, before the counters are prepared), so
+// the ranking rounds do not each wait for a load.
+constexpr int CHUNK_ROUNDS = PERM_CHUNK / 64;
+
+__device__ __forceinline__ void load_chunk_keys(const int32_t *__restrict__ keys, int64_t n_items, int chunk, int lane,
+                                                int (&g)[CHUNK_ROUNDS]) {
+    const int64_t a0 = (int64_t)chunk * PERM_CHUNK;
+#pragma unroll
+    for (int q = 0; q < CHUNK_ROUNDS; ++q) {
+        const int64_t a = a0 + q * 64 + lane;
+        g[q] = a < n_items ? keys[a] : -1;
+    }
+}
+
+__device__ __forceinline__ void rank_chunk(const int (&g_in)[CHUNK_ROUNDS], int64_t n_items, int nkeys, int32_t *cnt,
                                            int32_t *__restrict__ perm_pos, int32_t *__restrict__ perm_src, int nbits,
                                            int src_div, int chunk, int lane) {
     const int64_t a0 = (int64_t)chunk * PERM_CHUNK;
     const int64_t a1 = min(n_items, a0 + PERM_CHUNK);
     const uint64_t lt = lanemask_lt();
-    for (int64_t b = a0; b < a1; b += 64) {
-        const int64_t a = b + lane;
+#pragma unroll
+    for (int q = 0; q < CHUNK_ROUNDS; ++q) {
+        const int64_t a = a0 + q * 64 + lane;
+        if (a0 + q * 64 >= a1) break;  // uniform
         const bool in = a < a1;
-        const int g = in ? keys[a] : 0;
+        const int g = in ? g_in[q] : 0;
         const bool valid = in && (unsigned)g < (unsigned)nkeys;
         const uint64_t same = wave_match((uint32_t)g, valid, nbits);
         if (valid) {
@@ -107,9 +123,11 @@ static __global__ __launch_bounds__(64) void key_pos_kernel(const int32_t *__res
     __shared__ int32_t cnt[GRACE_MAX_INSTANCES];
     const int lane = (int)threadIdx.x;
     const int chunk = (int)blockIdx.x;
+    int g[CHUNK_ROUNDS];
+    load_chunk_keys(topk_inst, n_assign, chunk, lane, g);
     for (int i = lane; i < I; i += 64) cnt[i] = inst_off[i] + chunk_base[(size_t)chunk * I + i];
     __syncthreads();
-    rank_chunk(topk_inst, n_assign, I, cnt, perm_pos, perm_src, nbits, src_div, chunk, lane);
+    rank_chunk(g, n_assign, I, cnt, perm_pos, perm_src, nbits, src_div, chunk, lane);
 }
 
 // The scan folded into the position kernel, for few chunks: every block derives its offsets from
@@ -130,6 +148,8 @@ static __global__ __launch_bounds__(POS_FOLD_THREADS) void key_pos_fold_kernel(
     __shared__ int32_t off[GRACE_MAX_INSTANCES + 1];  // items of each key in all chunks, then exclusive offsets
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int chunk = (int)blockIdx.x;
+    int g[CHUNK_ROUNDS];
+    if (wave == 0) load_chunk_keys(keys, n_items, chunk, lane, g);  // in flight while the histograms are summed
     for (int i = tid; i < I; i += POS_FOLD_THREADS) {
         cnt[i] = 0;
         off[i] = 0;
@@ -191,7 +211,7 @@ static __global__ __launch_bounds__(POS_FOLD_THREADS) void key_pos_fold_kernel(
         if (node_off)
             for (int n = lane; n <= N; n += 64) node_off[n] = off[node_first_inst[n]];
     }
-    rank_chunk(keys, n_items, I, cnt, perm_pos, perm_src, nbits, src_div, chunk, lane);
+    rank_chunk(g, n_items, I, cnt, perm_pos, perm_src, nbits, src_div, chunk, lane);
 }
 
 // Host side: the launches of one stable counting sort.  hist / base: workspace of nchunks * nkeys
