@@ -252,6 +252,10 @@ def main() -> int:
     else:
         result["stages_achieved"]["route_GBs"] = bytes_route / (stage_ms["route"] * 1e-3) / 1e9
         result["stages_achieved"]["permute_GBs"] = bytes_permute / (stage_ms["permute"] * 1e-3) / 1e9
+    # the HBM-bound calls together: algorithmic bytes of routing, permutation and combine over their summed time
+    t_hbm = stage_ms["combine"] + (stage_ms["route_permute"] if "route_permute" in stage_ms
+                                   else stage_ms["route"] + stage_ms["permute"])
+    result["stages_achieved"]["route_permute_combine_GBs"] = (bytes_route + bytes_permute + bytes_combine) / (t_hbm * 1e-3) / 1e9
     if sh is not None:
         result["stages_achieved"]["shared_ffn_TFLOPs"] = 6.0 * d * f * cfg.n_shared * T / (stage_ms["shared_ffn"] * 1e-3) / 1e12
     if cfg.dtype == "bf16":
