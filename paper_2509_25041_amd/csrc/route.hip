@@ -34,7 +34,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *__restr
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (int i = tid; i < E; i += TOPK_THREADS) hist[i] = 0;
     // counters a later kernel of the same call accumulates into
-    for (int i = (int)blockIdx.x * TOPK_THREADS + tid; i < n_clear; i += (int)gridDim.x * TOPK_THREADS) clear[i] = 0;
+    for (int64_t i = (int64_t)blockIdx.x * TOPK_THREADS + tid; i < n_clear; i += (int64_t)gridDim.x * TOPK_THREADS) clear[i] = 0;
     __syncthreads();
     const int chunk = (int)blockIdx.x;
     const int t_begin = (chunk * (TOPK_THREADS / 64) + wave) * TOPK_TOK_PER_WAVE;

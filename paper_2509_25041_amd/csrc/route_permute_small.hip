@@ -173,7 +173,9 @@ extern "C" int grace_route_permute(const grace_table *table, int32_t local_rank,
     rc = check_permute_args(table, topk_inst, T, k, x, d, dt, perm_pos, perm_src, inst_off, rank_off, node_off, xp, ws);
     if (rc != GRACE_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
-    if (T == 0) {
+    // the shared-histogram path counts with 32-bit indices; sizes beyond that take the two calls
+    const bool hist_fits = ceil_div((int64_t)T * k, PERM_CHUNK) * table->I <= (int64_t)1 << 30;
+    if (T == 0 || !hist_fits) {
         rc = grace_route(table, local_rank, policy, logits, T, E, k, renorm, rr_in, rr_out, topk_expert, topk_weight,
                          topk_inst, expert_count, ws, stream);
         if (rc != GRACE_OK) return rc;
