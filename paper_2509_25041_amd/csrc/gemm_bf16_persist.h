@@ -38,7 +38,9 @@
 // block b runs on XCD b % 8 (checked with HW_REG_XCC_ID).  Each XCD owns a
 // contiguous range of m-tiles and its workgroups take consecutive (m-tile,
 // n-tile) pairs, so at any time an XCD works on a few m-tiles x all n-tiles
-// and shares their operands in its own L2.
+// and shares their operands in its own L2.  When whole m-tiles cannot be dealt
+// evenly (few m-tiles, many n-tiles) the pairs are instead numbered with the
+// shorter axis fastest and cut into eight equal ranges.
 #pragma once
 #include <type_traits>
 
@@ -104,11 +106,33 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     auto lookup = [&](int mt) { return segs.lookup(mt, lane); };
 
     // ---- this workgroup's tiles ------------------------------------------------------------
+    // Two ways to split the (m-tile, n-tile) pairs over the XCDs; the workgroups of an XCD take
+    // consecutive pairs of its share.
+    //  * by m-tile: an XCD owns a contiguous range of m-tiles with all their n-tiles (shares end on
+    //    m-tile boundaries, so a row block is read by one L2 only);
+    //  * flat: the pairs, numbered with the shorter axis running fastest, are cut into eight equal
+    //    contiguous ranges.  Taken when it needs fewer rounds of tiles, i.e. when whole m-tiles
+    //    cannot be dealt evenly (few m-tiles with many n-tiles).
     const int nblk = (int)gridDim.x / N_XCD;                          // workgroups per XCD
     const int xcd = (int)blockIdx.x % N_XCD, bslot = (int)blockIdx.x / N_XCD;
     const int mt_each = total_mt / N_XCD, mt_rem = total_mt % N_XCD;  // first mt_rem XCDs take one more
     const int mt_first = xcd * mt_each + min(xcd, mt_rem);
-    const int njobs = (mt_each + (xcd < mt_rem ? 1 : 0)) * n_tiles_n;
+    const int n_pairs = total_mt * n_tiles_n;                         // < 2^31 (checked by the launcher)
+    const int j_each = n_pairs / N_XCD, j_rem = n_pairs % N_XCD;      // first j_rem XCDs take one more
+    const int j_first = xcd * j_each + min(xcd, j_rem);
+    const int rounds_m = ((mt_each + (mt_rem ? 1 : 0)) * n_tiles_n + nblk - 1) / nblk;
+    const int rounds_f = (j_each + (j_rem ? 1 : 0) + nblk - 1) / nblk;
+    const bool flat = rounds_f < rounds_m;                            // uniform
+    const bool m_fastest = n_tiles_n > total_mt;
+    const int njobs = flat ? j_each + (xcd < j_rem ? 1 : 0) : (mt_each + (xcd < mt_rem ? 1 : 0)) * n_tiles_n;
+    auto job_mt = [&](int job) {
+        const int q = j_first + job;
+        return flat ? (m_fastest ? q % total_mt : q / n_tiles_n) : mt_first + job / n_tiles_n;
+    };
+    auto job_n0 = [&](int job) {
+        const int q = j_first + job;
+        return (flat ? (m_fastest ? q / total_mt : q % n_tiles_n) : job % n_tiles_n) * BN;
+    };
     int job = bslot;
     if (job >= njobs) return;
 
@@ -379,8 +403,8 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     // ---- tile loop ----------------------------------------------------------------------------------
     // Per tile of nk steps: steps 0 .. nk-3 load this tile's steps 2 .. nk-1; steps nk-2 and nk-1
     // load steps 0 and 1 of the next tile, if there is one.
-    Tile cur = lookup(mt_first + job / n_tiles_n);
-    int cur_n0 = (job % n_tiles_n) * BN;
+    Tile cur = lookup(job_mt(job));
+    int cur_n0 = job_n0(job);
     set_a_sources(cur);
     set_b_sources(cur, cur_n0);
     issue_a();
@@ -395,8 +419,8 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
         Tile nxt = cur;
         int nxt_n0 = cur_n0;
         if (has_next) {
-            nxt = lookup(mt_first + next_job / n_tiles_n);
-            nxt_n0 = (next_job % n_tiles_n) * BN;
+            nxt = lookup(job_mt(next_job));
+            nxt_n0 = job_n0(next_job);
         }
         // 32-row sub-tiles of this wavefront that hold at least one valid row (scalar)
         const int n_valid = max(0, min(4, (cur.m_end - (cur.m0 + wm * 128) + 31) / 32));
