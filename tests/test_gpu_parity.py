@@ -372,6 +372,27 @@ def test_many_tiles_per_workgroup_element_by_element():
     assert not host(y)[:lo].any() and not host(y)[hi:].any()      # rows of the other rank untouched
 
 
+def test_few_row_tiles_many_column_tiles_element_by_element():
+    """Two m-tiles with 36 (up) and 33 (down) n-tiles: dealing whole m-tiles to the XCDs would take
+    two rounds of tiles, so the GEMM cuts the (m-tile, n-tile) pairs flat into eight ranges with the
+    m index running fastest."""
+    cfg = LayerConfig("bf16_wide", T=300, E=2, k=1, d=8448, f=4608, dtype="bf16", zipf_s=0.5, nodes=1,
+                      gpus_per_node=1, n_hot=1, replica_mode="all", seed=23)
+    wl = make_workload(cfg)
+    pl = wl.placement
+    ref = oracle.route_permute(wl.logits, pl, cfg.k, 0)
+    table, g = run_route_permute(wl, pl, cfg.k, 0)
+    check_route_permute(g, ref, wl, cfg.k)
+    seg = np.diff(ref.perm.inst_off)
+    m_tiles = sum(-(-int(m) // 256) for m in seg)
+    assert m_tiles == 2 and cfg.f // 128 > 32 and cfg.d // 256 > 32
+    wg, wu, wd = _stack_dev(wl, table.local_experts(0))
+    y = grace.grace_expert_ffn(table, 0, g.xp, g.ioff, cfg.T, cfg.k, wg, wu, wd)
+    torch.cuda.synchronize()
+    want = oracle.expert_ffn(ref, oracle.widen(wl.x), cfg.k, [0], _weights64(wl), threads=8)
+    assert rel_err(oracle.widen(host(y)), want) <= TOL["bf16"]
+
+
 def test_more_than_64_local_slots_element_by_element():
     """A rank hosting more than 64 expert instances (four row segments per lane in the GEMM's
     segment table), many of them empty or a few rows long."""
