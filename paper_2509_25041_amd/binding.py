@@ -17,7 +17,8 @@ _STATUS = {0: "GRACE_OK", -1: "GRACE_EINVAL", -2: "GRACE_ESHAPE", -3: "GRACE_ETA
 
 EXPORTS = ("grace_table_validate", "grace_table_create", "grace_table_destroy", "grace_table_info",
            "grace_table_instances", "grace_table_local_experts", "grace_workspace_bytes", "grace_route",
-           "grace_permute", "grace_route_permute", "grace_send_lists", "grace_expert_ffn", "grace_expert_ffn_up", "grace_expert_ffn_down", "grace_shared_ffn", "grace_combine", "grace_mfma_sustained", "grace_last_error")
+           "grace_permute", "grace_route_permute", "grace_send_lists", "grace_expert_ffn", "grace_expert_ffn_up",
+           "grace_expert_ffn_down", "grace_shared_ffn", "grace_combine", "grace_mfma_sustained", "grace_last_error")
 
 _lib: Optional[C.CDLL] = None
 
@@ -53,6 +54,8 @@ def load_library() -> C.CDLL:
     lib.grace_workspace_bytes.argtypes = [i32] * 7 + [C.c_int]
     lib.grace_route.argtypes = [vp, i32, C.c_int, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.grace_permute.argtypes = [vp, vp, i32, i32, vp, i32, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.grace_route_permute.argtypes = [vp, i32, C.c_int, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp,
+                                        vp, i32, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.grace_send_lists.argtypes = [vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.grace_expert_ffn.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp, vp]
     lib.grace_expert_ffn_up.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp]
@@ -213,7 +216,7 @@ def grace_permute(table: GraceTable, topk_inst: torch.Tensor, x: Optional[torch.
 def grace_route_permute(table: GraceTable, local_rank: int, logits: torch.Tensor, k: int, x: Optional[torch.Tensor],
                         renorm: int = 1, rr_in: Optional[torch.Tensor] = None, rr_out: Optional[torch.Tensor] = None,
                         ws: Optional[torch.Tensor] = None, policy: int = GRACE_POLICY_TAR):
-    """grace_route and grace_permute as one call (one single-workgroup kernel for decode-sized batches).
+    """grace_route and grace_permute as one call with fewer launches (see grace_moe.h).
     -> ((topk_expert, topk_weight, topk_inst, expert_count), (perm_pos, perm_src, inst_off, rank_off, node_off, xp))."""
     T, E = logits.shape
     dev = logits.device
