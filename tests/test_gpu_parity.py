@@ -2,6 +2,7 @@
 seeded inputs.  Integer outputs bit-exact; gate weights within 1e-6 relative;
 FFN / combine outputs within 2e-2 (bf16) / 1e-5 (fp32) by the metric
 max |y - r| / max(|r|, rms(r))."""
+import sys
 from types import SimpleNamespace
 
 import numpy as np
@@ -550,3 +551,20 @@ def test_full_size_rank_share_sampled(name):
         assert not bool(layer.y[:lo].any())
     if hi < cfg.T * cfg.k:
         assert not bool(layer.y[hi:].any())
+
+
+def test_routing_report_runs_and_is_consistent(capsys, monkeypatch):
+    """routing_report.py (replication and policy ablation on one GPU): totals add up, de-duplication never
+    adds traffic, and locality-first routing sends no more rows across nodes than round-robin over all
+    instances."""
+    import json
+    import routing_report
+    monkeypatch.setattr(sys, "argv", ["routing_report.py", "--workload", "tiny"])
+    assert routing_report.main() == 0
+    lines = [json.loads(l) for l in capsys.readouterr().out.strip().splitlines()]
+    assert [l["setup"] for l in lines] == ["no replicas", "replicas, weighted round-robin", "replicas, locality first"]
+    cfg = CONFIGS["tiny"]
+    for l in lines:
+        assert l["rows_per_rank"]["mean"] * l["ranks"] == cfg.T * cfg.k * l["ranks"]
+        assert l["cross_node_tokens"]["dedup"] <= l["cross_node_tokens"]["one_row_per_assignment"]
+    assert lines[2]["cross_node_tokens"]["one_row_per_assignment"] <= lines[1]["cross_node_tokens"]["one_row_per_assignment"]
