@@ -181,8 +181,8 @@ int grace_route_permute(const grace_table *table, int32_t local_rank, grace_poli
                         int32_t *inst_off, int32_t *rank_off, int32_t *node_off, void *xp, void *ws, void *stream);
 
 /* ---- grace_send_lists: de-duplicated hierarchical send lists ------------------
- * Section 5: a token routed to several experts on the same destination is
- * transmitted only once.  For the T tokens of local_rank and their instance ids
+ * Section 5: a token with several experts on one destination crosses the link
+ * to that destination a single time.  For the T tokens of local_rank and their instance ids
  * (from grace_route) this builds
  *   rank_send_ptr [R+1], rank_send_tok : for every destination rank the ascending list of
  *       distinct tokens with at least one assignment there (what stage 2 delivers to it);

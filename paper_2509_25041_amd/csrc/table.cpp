@@ -240,7 +240,8 @@ extern "C" size_t grace_workspace_bytes(int32_t T, int32_t E, int32_t k, int32_t
     size_t need = grace::fused_perm_ws_offset(T, E) + 2 * grace::align_up(chunks_p * (size_t)I * 4, 256);
     need = std::max(need, grace::align_up(n * (size_t)f * el, 256));
     need = std::max(need, grace::align_up((size_t)T * (size_t)n_shared * (size_t)f * el, 256));
-    // send lists: five int32 arrays over the assignments + chunk histograms over up to GRACE_MAX_RANKS keys
-    need = std::max(need, 5 * grace::align_up(n * 4, 256) + 2 * grace::align_up(chunks_p * (size_t)GRACE_MAX_RANKS * 4, 256));
+    // send lists: five int32 arrays over the assignments + chunk histograms over up to GRACE_MAX_RANKS keys + counters
+    need = std::max(need, 5 * grace::align_up(n * 4, 256) + 2 * grace::align_up(chunks_p * (size_t)GRACE_MAX_RANKS * 4, 256) +
+                              grace::align_up(((size_t)GRACE_MAX_RANKS + 1) * 4, 256));
     return need + 256;
 }
