@@ -394,6 +394,33 @@ def test_few_row_tiles_many_column_tiles_element_by_element():
     assert rel_err(oracle.widen(host(y)), want) <= TOL["bf16"]
 
 
+def test_few_tiles_long_k_element_by_element():
+    """Two m-tiles, 32 (up) and 16 (down) n-tiles, 64 K steps each: fewer tiles than compute units and
+    a long K (the shape of mixtral's projections at a small batch), expert and shared FFN."""
+    cfg = LayerConfig("bf16_long_k", T=300, E=2, k=1, d=4096, f=4096, dtype="bf16", zipf_s=0.5, nodes=1,
+                      gpus_per_node=1, n_hot=1, replica_mode="all", n_shared=1, seed=24)
+    wl = make_workload(cfg)
+    pl = wl.placement
+    ref = oracle.route_permute(wl.logits, pl, cfg.k, 0)
+    table, g = run_route_permute(wl, pl, cfg.k, 0)
+    check_route_permute(g, ref, wl, cfg.k)
+    seg = np.diff(ref.perm.inst_off)
+    m_tiles = sum(-(-int(m) // 256) for m in seg)
+    assert m_tiles * (cfg.f // 128) < 256 and cfg.d // 64 >= 64 and cfg.f // 64 >= 64
+    wg, wu, wd = _stack_dev(wl, table.local_experts(0))
+    y = grace.grace_expert_ffn(table, 0, g.xp, g.ioff, cfg.T, cfg.k, wg, wu, wd)
+    torch.cuda.synchronize()
+    x64 = oracle.widen(wl.x)
+    want = oracle.expert_ffn(ref, x64, cfg.k, [0], _weights64(wl), threads=8)
+    assert rel_err(oracle.widen(host(y)), want) <= TOL["bf16"]
+    # the shared expert's FFN on the same shape: one segment of 300 rows, K segments in the down projection
+    sh = wl.shared_weights()
+    ys = grace.grace_shared_ffn(g.x, *[dev(w) for w in sh])
+    torch.cuda.synchronize()
+    ys_ref = oracle.shared_ffn(x64, tuple(oracle.widen(w) for w in sh))
+    assert rel_err(oracle.widen(host(ys)), ys_ref) <= TOL["bf16"]
+
+
 def test_more_than_64_local_slots_element_by_element():
     """A rank hosting more than 64 expert instances (four row segments per lane in the GEMM's
     segment table), many of them empty or a few rows long."""
