@@ -203,7 +203,7 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
 }
 
 // Few chunks: a pick block can afford to sum the histograms before its own.
-constexpr int ROUTE_FOLD_MAX_LOADS = 1024;
+constexpr int ROUTE_FOLD_MAX_LOADS = 8192;
 inline bool fold_route_scan(int nchunks, int E) { return nchunks >= 1 && (int64_t)nchunks * ((E + 63) / 64) <= ROUTE_FOLD_MAX_LOADS; }
 
 }  // namespace grace

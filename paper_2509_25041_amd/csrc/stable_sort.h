@@ -134,7 +134,7 @@ static __global__ __launch_bounds__(64) void key_pos_kernel(const int32_t *__res
 // the chunk histograms itself (totals over all chunks -> exclusive scan over keys, plus the counts
 // of the chunks before its own), which saves the single-block scan launch; block 0 also writes
 // the offset outputs.  Work per block grows with nchunks * nkeys, hence the bound below.
-constexpr int FOLD_MAX_LOADS = 1024;  // histogram loads a block may spend per key column on its own scan
+constexpr int FOLD_MAX_LOADS = 8192;  // histogram loads a block may spend per key column on its own scan
 inline bool fold_scan(int nchunks, int nkeys) { return nchunks >= 1 && (int64_t)nchunks * ((nkeys + 63) / 64) <= FOLD_MAX_LOADS; }
 
 constexpr int POS_FOLD_THREADS = 512;  // all eight wavefronts sum histogram rows; wavefront 0 scans and ranks

@@ -93,13 +93,16 @@ def test_route_and_permute_bit_exact(name, T, local_rank):
     check_route_permute(g, ref, wl, cfg.k)
 
 
-def test_route_and_permute_many_chunks_separate_scan_kernels():
-    """Enough chunks that the scans run as kernels of their own instead of inside the pick /
-    position kernels (route: > 1024 chunk rows per expert column; permute likewise)."""
-    cfg = LayerConfig("many_chunks", T=50000, E=128, k=8, d=8, f=16, dtype="f32", zipf_s=1.2, nodes=2,
+@pytest.mark.parametrize("T,scan_kernels", [(50000, False), (180000, True)])
+def test_route_and_permute_many_chunks(T, scan_kernels):
+    """Many chunks: at 50 000 tokens every pick / position block still sums the histogram rows before
+    its own chunk itself (thousands of rows); at 180 000 the scans run as kernels of their own
+    (route: > 8192 chunk rows per expert column; permute likewise)."""
+    cfg = LayerConfig("many_chunks", T=T, E=128, k=8, d=8, f=16, dtype="f32", zipf_s=1.2, nodes=2,
                       gpus_per_node=4, n_hot=8, replica_mode="per_node", seed=31)
     wl = make_workload(cfg)
-    assert -(-cfg.T // 32) * 2 > 1024 and -(-cfg.T * cfg.k // 512) * -(-wl.placement.I // 64) > 1024
+    beyond = -(-cfg.T // 32) * 2 > 8192 and -(-cfg.T * cfg.k // 512) * -(-wl.placement.I // 64) > 8192
+    assert beyond == scan_kernels
     ref = oracle.route_permute(wl.logits, wl.placement, cfg.k, 3)
     _, g = run_route_permute(wl, wl.placement, cfg.k, 3)
     check_route_permute(g, ref, wl, cfg.k)
