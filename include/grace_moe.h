@@ -109,6 +109,16 @@ int grace_table_instances(const grace_table *table, int32_t *inst_expert, int32_
  * experts_out must hold max_local_slots entries. */
 int grace_table_local_experts(const grace_table *table, int32_t rank, int32_t *experts_out, int32_t *n_out);
 
+/* Tuning: where the routing and permutation index kernels switch algorithm.  They turn per-chunk
+ * histograms (chunks of 16 or 32 tokens in grace_route, of 512 assignments in grace_permute and
+ * grace_send_lists) into prefix counts: up to one_level_max histogram loads per column of 64 keys
+ * (chunks * ceil(keys / 64)) every block sums the rows before its own chunk; up to two_level_max
+ * loads (of super-chunk sums of 64 rows plus the rows of the own super-chunk) it uses those
+ * two-level sums, one more launch; beyond that, single-block scan kernels.  Results are identical
+ * on every path.  A negative value restores the default (1024, 8192).  Process-wide; affects
+ * calls made afterwards.  Always returns GRACE_OK. */
+int grace_set_fold_limits(int32_t one_level_max, int32_t two_level_max);
+
 /* Bytes of device scratch that any single call below needs for these sizes
  * (the same buffer may be reused by consecutive calls on one stream).
  * f and n_shared may be 0 when the FFN entry points are not used.  Returns 0

@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     grace_route,
     grace_route_permute,
     grace_send_lists,
+    grace_set_fold_limits,
     grace_shared_ffn,
     grace_table_validate,
     grace_workspace_bytes,

@@ -16,7 +16,7 @@ _STATUS = {0: "GRACE_OK", -1: "GRACE_EINVAL", -2: "GRACE_ESHAPE", -3: "GRACE_ETA
            -5: "GRACE_EHIP"}
 
 EXPORTS = ("grace_table_validate", "grace_table_create", "grace_table_destroy", "grace_table_info",
-           "grace_table_instances", "grace_table_local_experts", "grace_workspace_bytes", "grace_route",
+           "grace_table_instances", "grace_table_local_experts", "grace_set_fold_limits", "grace_workspace_bytes", "grace_route",
            "grace_permute", "grace_route_permute", "grace_send_lists", "grace_expert_ffn", "grace_expert_ffn_up",
            "grace_expert_ffn_down", "grace_shared_ffn", "grace_combine", "grace_mfma_sustained", "grace_last_error")
 
@@ -50,6 +50,7 @@ def load_library() -> C.CDLL:
     lib.grace_table_info.argtypes = [vp] + [C.POINTER(i32)] * 5
     lib.grace_table_instances.argtypes = [vp, vp, vp, vp]
     lib.grace_table_local_experts.argtypes = [vp, i32, vp, C.POINTER(i32)]
+    lib.grace_set_fold_limits.argtypes = [i32, i32]
     lib.grace_workspace_bytes.restype = u64
     lib.grace_workspace_bytes.argtypes = [i32] * 7 + [C.c_int]
     lib.grace_route.argtypes = [vp, i32, C.c_int, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -112,6 +113,11 @@ def grace_table_validate(E, R, N, rank_node, poll_weight, inst_ptr, inst_rank) -
     a = (_host(rank_node, np.int32), _host(poll_weight, np.uint32), _host(inst_ptr, np.int32),
          _host(inst_rank, np.int32))
     _check(load_library().grace_table_validate(E, R, N, *[_hp(x) for x in a]))
+
+
+def grace_set_fold_limits(one_level_max: int = -1, two_level_max: int = -1) -> None:
+    """Switch points of the index kernels' prefix-count algorithms (negative: defaults); see grace_moe.h."""
+    _check(load_library().grace_set_fold_limits(one_level_max, two_level_max))
 
 
 def grace_workspace_bytes(T, E, k, I, d=0, f=0, n_shared=0, dt=GRACE_BF16) -> int:

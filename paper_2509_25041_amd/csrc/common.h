@@ -40,6 +40,13 @@ inline int route_chunk_tokens(int T) { return T <= ROUTE_SMALL_CHUNK_MAX_T ? ROU
 constexpr int PERM_CHUNK = 512;              // permute: chunk = 512 assignments
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// How the index kernels turn chunk histograms into prefix counts (grace_set_fold_limits moves the
+// switch points).  0: separate single-block scan kernels; 1: every block sums the rows before its
+// chunk; 2: two-level sums (super-chunks of 64 rows, one extra launch).
+constexpr int FOLD_ONE_LEVEL_DEFAULT = 1024;  // histogram loads per key column a block may spend on a one-level sum
+constexpr int FOLD_TWO_LEVEL_DEFAULT = 8192;  // the same for the super rows + chunk rows of a two-level sum
+int fold_mode(int nchunks, int nkeys);
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace grace

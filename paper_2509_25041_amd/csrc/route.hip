@@ -110,7 +110,8 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
                                                             const int32_t *__restrict__ cand_g,
                                                             const uint32_t *__restrict__ cand_cum,
                                                             int32_t *__restrict__ topk_inst, int nbits,
-                                                            int chunk_tokens, int32_t *__restrict__ inst_hist, int I) {
+                                                            int chunk_tokens, int32_t *__restrict__ inst_hist, int I,
+                                                            const int32_t *__restrict__ super_tot) {
     __shared__ uint32_t cnt[GRACE_MAX_EXPERTS];
     __shared__ int32_t s_ptr[GRACE_MAX_EXPERTS + 1];  // this view's candidate lists, offsets from its first entry
     __shared__ int32_t s_g[PICK_LDS_CANDS];
@@ -140,26 +141,17 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
         }
     }
     if (FOLD) {
-        // requests before this chunk: the wavefronts share the histogram rows 0 .. chunk-1
+        // requests before this chunk: the wavefronts share the histogram rows 0 .. chunk-1, or, with
+        // super_tot, the super rows before the chunk's super-chunk and the chunk rows inside it
         for (int e = tid; e < E; e += PICK_THREADS) cnt[e] = 0;
         __syncthreads();
         constexpr int NW = PICK_THREADS / 64;
-        const int nkb = (E + 63) / 64;  // blocks of 64 experts; a wavefront stays on one when nkb divides NW
-        if (NW % nkb == 0) {
-            const int e = (wave % nkb) * 64 + lane, rstep = NW / nkb;
-            if (e < E) {
-                int32_t part = 0;
-#pragma unroll 8
-                for (int c = wave / nkb; c < chunk; c += rstep) part += chunk_counts[(size_t)c * E + e];
-                if (part) atomicAdd(&cnt[e], (uint32_t)part);  // integer sum: order does not matter
-            }
+        if (super_tot) {
+            const int s = chunk / FOLD_SUPER;
+            block_add_rows<NW>(super_tot, 0, s, E, (int32_t *)cnt, wave, lane);
+            block_add_rows<NW>(chunk_counts, s * FOLD_SUPER, chunk, E, (int32_t *)cnt, wave, lane);
         } else {
-            for (int e = lane; e < E; e += 64) {
-                int32_t part = 0;
-#pragma unroll 8
-                for (int c = wave; c < chunk; c += NW) part += chunk_counts[(size_t)c * E + e];
-                if (part) atomicAdd(&cnt[e], (uint32_t)part);
-            }
+            block_add_rows<NW>(chunk_counts, 0, chunk, E, (int32_t *)cnt, wave, lane);
         }
         __syncthreads();
         if (chunk == nchunks - 1) {
@@ -201,10 +193,6 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
         }
     }
 }
-
-// Few chunks: a pick block can afford to sum the histograms before its own.
-constexpr int ROUTE_FOLD_MAX_LOADS = 8192;
-inline bool fold_route_scan(int nchunks, int E) { return nchunks >= 1 && (int64_t)nchunks * ((E + 63) / 64) <= ROUTE_FOLD_MAX_LOADS; }
 
 }  // namespace grace
 
@@ -277,10 +265,17 @@ int launch_route(const grace_table *table, int32_t local_rank, grace_policy poli
     }
     int nbits = 0;
     while ((1 << nbits) < E) ++nbits;
-    if (fold_route_scan(nchunks, E)) {
+    const int mode = fold_mode(nchunks, E);
+    if (mode != 0) {
+        const int32_t *super_tot = nullptr;
+        if (mode == 2) {  // column sums per super-chunk of rows, into the (otherwise unused) scan buffer
+            super_sum_kernel<<<(unsigned)ceil_div(nchunks, FOLD_SUPER), SUPER_THREADS, 0, st>>>(hist, nchunks, E, base);
+            GRACE_LAUNCH_CHECK("super_sum_kernel");
+            super_tot = base;
+        }
         pick_kernel<true><<<nchunks, PICK_THREADS, 0, st>>>(topk_expert, (int64_t)T * k, E, k, hist, nchunks, rr_in, rr_out,
                                                   expert_count, cand_ptr, table->d_cand_g, table->d_cand_cum, topk_inst,
-                                                  nbits, chunk_tokens, inst_hist, I);
+                                                  nbits, chunk_tokens, inst_hist, I, super_tot);
         GRACE_LAUNCH_CHECK("pick_kernel");
         return GRACE_OK;
     }
@@ -290,7 +285,7 @@ int launch_route(const grace_table *table, int32_t local_rank, grace_policy poli
     if (nchunks > 0) {
         pick_kernel<false><<<nchunks, PICK_THREADS, 0, st>>>(topk_expert, (int64_t)T * k, E, k, base, nchunks, rr_in, rr_out,
                                                    expert_count, cand_ptr, table->d_cand_g, table->d_cand_cum, topk_inst,
-                                                   nbits, chunk_tokens, inst_hist, I);
+                                                   nbits, chunk_tokens, inst_hist, I, nullptr);
         GRACE_LAUNCH_CHECK("pick_kernel");
     }
     return GRACE_OK;

@@ -130,20 +130,19 @@ static __global__ __launch_bounds__(64) void key_pos_kernel(const int32_t *__res
     rank_chunk(g, n_assign, I, cnt, perm_pos, perm_src, nbits, src_div, chunk, lane);
 }
 
-// The scan folded into the position kernel, for few chunks: every block derives its offsets from
-// the chunk histograms itself (totals over all chunks -> exclusive scan over keys, plus the counts
-// of the chunks before its own), which saves the single-block scan launch; block 0 also writes
-// the offset outputs.  Work per block grows with nchunks * nkeys, hence the bound below.
-constexpr int FOLD_MAX_LOADS = 8192;  // histogram loads a block may spend per key column on its own scan
-inline bool fold_scan(int nchunks, int nkeys) { return nchunks >= 1 && (int64_t)nchunks * ((nkeys + 63) / 64) <= FOLD_MAX_LOADS; }
-
+// The scan folded into the position kernel: every block derives its offsets from the chunk
+// histograms itself (totals over all chunks -> exclusive scan over keys, plus the counts of the
+// chunks before its own), which saves the single-block scan launch; block 0 also writes the offset
+// outputs.  With super_tot (column sums per FOLD_SUPER chunk rows) the block reads the super rows
+// and the chunk rows of its own super-chunk instead of every row.
 constexpr int POS_FOLD_THREADS = 512;  // all eight wavefronts sum histogram rows; wavefront 0 scans and ranks
 
 static __global__ __launch_bounds__(POS_FOLD_THREADS) void key_pos_fold_kernel(
     const int32_t *__restrict__ keys, int64_t n_items, int I, const int32_t *__restrict__ chunk_hist, int nchunks, int R,
     int N, const int32_t *__restrict__ rank_ptr, const int32_t *__restrict__ node_first_inst,
     int32_t *__restrict__ inst_off, int32_t *__restrict__ rank_off, int32_t *__restrict__ node_off,
-    int32_t *__restrict__ perm_pos, int32_t *__restrict__ perm_src, int nbits, int src_div) {
+    int32_t *__restrict__ perm_pos, int32_t *__restrict__ perm_src, int nbits, int src_div,
+    const int32_t *__restrict__ super_tot) {
     __shared__ int32_t cnt[GRACE_MAX_INSTANCES];      // items of each key in the chunks before this one, then positions
     __shared__ int32_t off[GRACE_MAX_INSTANCES + 1];  // items of each key in all chunks, then exclusive offsets
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -155,34 +154,41 @@ static __global__ __launch_bounds__(POS_FOLD_THREADS) void key_pos_fold_kernel(
         off[i] = 0;
     }
     __syncthreads();
-    // (block of 64 keys, histogram row) pairs are dealt to the wavefronts; when the number of key
-    // blocks divides the number of wavefronts each wavefront stays on one key block
     constexpr int NW = POS_FOLD_THREADS / 64;
-    const int nkb = (I + 63) / 64;
-    if (NW % nkb == 0) {
-        const int key = (wave % nkb) * 64 + lane, rstep = NW / nkb;
-        if (key < I) {
-            int32_t tot = 0, prev = 0;
-#pragma unroll 8
-            for (int c = wave / nkb; c < nchunks; c += rstep) {
-                const int32_t v = chunk_hist[(size_t)c * I + key];
-                tot += v;
-                prev += (c < chunk) ? v : 0;
-            }
-            if (tot) atomicAdd(&off[key], tot);  // integer sums: order does not matter
-            if (prev) atomicAdd(&cnt[key], prev);
-        }
+    if (super_tot) {
+        const int s = chunk / FOLD_SUPER, nsuper = (nchunks + FOLD_SUPER - 1) / FOLD_SUPER;
+        block_add_rows<NW>(super_tot, 0, nsuper, I, off, wave, lane);
+        block_add_rows<NW>(super_tot, 0, s, I, cnt, wave, lane);
+        block_add_rows<NW>(chunk_hist, s * FOLD_SUPER, chunk, I, cnt, wave, lane);
     } else {
-        for (int key = lane; key < I; key += 64) {
-            int32_t tot = 0, prev = 0;
+        // one pass over all rows gives both sums; (block of 64 keys, row) pairs are dealt to the
+        // wavefronts, each staying on one key block when the number of key blocks divides NW
+        const int nkb = (I + 63) / 64;
+        if (NW % nkb == 0) {
+            const int key = (wave % nkb) * 64 + lane, rstep = NW / nkb;
+            if (key < I) {
+                int32_t tot = 0, prev = 0;
 #pragma unroll 8
-            for (int c = wave; c < nchunks; c += NW) {
-                const int32_t v = chunk_hist[(size_t)c * I + key];
-                tot += v;
-                prev += (c < chunk) ? v : 0;
+                for (int c = wave / nkb; c < nchunks; c += rstep) {
+                    const int32_t v = chunk_hist[(size_t)c * I + key];
+                    tot += v;
+                    prev += (c < chunk) ? v : 0;
+                }
+                if (tot) atomicAdd(&off[key], tot);  // integer sums: order does not matter
+                if (prev) atomicAdd(&cnt[key], prev);
             }
-            if (tot) atomicAdd(&off[key], tot);
-            if (prev) atomicAdd(&cnt[key], prev);
+        } else {
+            for (int key = lane; key < I; key += 64) {
+                int32_t tot = 0, prev = 0;
+#pragma unroll 8
+                for (int c = wave; c < nchunks; c += NW) {
+                    const int32_t v = chunk_hist[(size_t)c * I + key];
+                    tot += v;
+                    prev += (c < chunk) ? v : 0;
+                }
+                if (tot) atomicAdd(&off[key], tot);
+                if (prev) atomicAdd(&cnt[key], prev);
+            }
         }
     }
     __syncthreads();
@@ -229,9 +235,16 @@ static inline const char *stable_sort_launch(const int32_t *keys, int64_t n, int
         key_hist_kernel<<<nchunks, 64, 0, st>>>(keys, n, nkeys, hist);
         if (hipGetLastError() != hipSuccess) return "key_hist_kernel";
     }
-    if (fold_scan(nchunks, nkeys)) {
+    const int mode = fold_mode(nchunks, nkeys);
+    if (mode != 0) {
+        const int32_t *super_tot = nullptr;
+        if (mode == 2) {  // column sums per super-chunk of rows, into the (otherwise unused) scan buffer
+            super_sum_kernel<<<(unsigned)ceil_div(nchunks, FOLD_SUPER), SUPER_THREADS, 0, st>>>(hist, nchunks, nkeys, base);
+            if (hipGetLastError() != hipSuccess) return "super_sum_kernel";
+            super_tot = base;
+        }
         key_pos_fold_kernel<<<nchunks, POS_FOLD_THREADS, 0, st>>>(keys, n, nkeys, hist, nchunks, R, N, rank_ptr, node_first_inst, off,
-                                                    rank_off, node_off, pos, src, nbits, src_div);
+                                                    rank_off, node_off, pos, src, nbits, src_div, super_tot);
         if (hipGetLastError() != hipSuccess) return "key_pos_fold_kernel";
         return nullptr;
     }

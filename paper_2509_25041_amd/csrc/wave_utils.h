@@ -54,6 +54,48 @@ __device__ __forceinline__ int bits_for(int nkeys) {
     return b;
 }
 
+// Column sums of rows [r0, r1) of a row-major [rows][nkeys] int32 matrix, added into acc[nkeys] (LDS,
+// initialised by the caller) by a block of NW wavefronts.  The rows are dealt to the wavefronts; a
+// wavefront stays on one block of 64 keys when the number of key blocks divides NW.  Integer
+// atomics: the result is exact in any order.
+template <int NW>
+__device__ __forceinline__ void block_add_rows(const int32_t *__restrict__ m, int r0, int r1, int nkeys, int32_t *acc,
+                                               int wave, int lane) {
+    const int nkb = (nkeys + 63) / 64;
+    if (NW % nkb == 0) {
+        const int key = (wave % nkb) * 64 + lane, rstep = NW / nkb;
+        if (key < nkeys) {
+            int32_t part = 0;
+#pragma unroll 8
+            for (int r = r0 + wave / nkb; r < r1; r += rstep) part += m[(size_t)r * nkeys + key];
+            if (part) atomicAdd(&acc[key], part);
+        }
+    } else {
+        for (int key = lane; key < nkeys; key += 64) {
+            int32_t part = 0;
+#pragma unroll 8
+            for (int r = r0 + wave; r < r1; r += NW) part += m[(size_t)r * nkeys + key];
+            if (part) atomicAdd(&acc[key], part);
+        }
+    }
+}
+
+// Two-level histogram sums: the chunk rows are grouped into super-chunks of FOLD_SUPER rows whose
+// column sums super_sum_kernel writes; a block then needs the super rows before its super-chunk and
+// the chunk rows inside it instead of every row before its chunk.
+constexpr int FOLD_SUPER = 64;
+constexpr int SUPER_THREADS = 512;
+static __global__ __launch_bounds__(SUPER_THREADS) void super_sum_kernel(const int32_t *__restrict__ hist, int nchunks,
+                                                                        int nkeys, int32_t *__restrict__ super_tot) {
+    __shared__ int32_t acc[4096];  // the largest key count of any caller (instances)
+    const int tid = (int)threadIdx.x, s = (int)blockIdx.x;
+    for (int i = tid; i < nkeys; i += SUPER_THREADS) acc[i] = 0;
+    __syncthreads();
+    block_add_rows<SUPER_THREADS / 64>(hist, s * FOLD_SUPER, min(nchunks, (s + 1) * FOLD_SUPER), nkeys, acc, tid >> 6, tid & 63);
+    __syncthreads();
+    for (int i = tid; i < nkeys; i += SUPER_THREADS) super_tot[(size_t)s * nkeys + i] = acc[i];
+}
+
 // Exclusive scan over chunks of a [nchunks][nkeys] histogram, per key:
 // base[c][key] = sum_{c' < c} hist[c'][key]; totals[key] = column sum (LDS or
 // global array of nkeys entries).  Must be called by a whole block of

@@ -93,20 +93,31 @@ def test_route_and_permute_bit_exact(name, T, local_rank):
     check_route_permute(g, ref, wl, cfg.k)
 
 
-@pytest.mark.parametrize("T,scan_kernels", [(50000, False), (180000, True)])
-def test_route_and_permute_many_chunks(T, scan_kernels):
-    """Many chunks: at 50 000 tokens every pick / position block still sums the histogram rows before
-    its own chunk itself (thousands of rows); at 180 000 the scans run as kernels of their own
-    (route: > 8192 chunk rows per expert column; permute likewise)."""
-    cfg = LayerConfig("many_chunks", T=T, E=128, k=8, d=8, f=16, dtype="f32", zipf_s=1.2, nodes=2,
+@pytest.mark.parametrize("limits", [(-1, -1), (1 << 30, -1), (0, -1), (0, 0)])
+def test_route_and_permute_many_chunks_every_prefix_algorithm(limits):
+    """50 000 tokens (1563 routing chunks, 782 permutation chunks) through each way of turning the
+    chunk histograms into prefix counts: the defaults (two-level sums at this size), one-level sums
+    forced (every block adds thousands of rows), two-level forced, and the single-block scan kernels.
+    Separate calls, the one-call dispatch and the send lists, all bit-exact."""
+    cfg = LayerConfig("many_chunks", T=50000, E=128, k=8, d=8, f=16, dtype="f32", zipf_s=1.2, nodes=2,
                       gpus_per_node=4, n_hot=8, replica_mode="per_node", seed=31)
     wl = make_workload(cfg)
-    beyond = -(-cfg.T // 32) * 2 > 8192 and -(-cfg.T * cfg.k // 512) * -(-wl.placement.I // 64) > 8192
-    assert beyond == scan_kernels
     ref = oracle.route_permute(wl.logits, wl.placement, cfg.k, 3)
-    _, g = run_route_permute(wl, wl.placement, cfg.k, 3)
-    check_route_permute(g, ref, wl, cfg.k)
-    check_route_permute(run_fused(wl, wl.placement, cfg.k, 3), ref, wl, cfg.k)   # the same as one call
+    sl = oracle.send_lists(ref.topk_inst, wl.placement, 3)
+    grace.grace_set_fold_limits(*limits)
+    try:
+        table, g = run_route_permute(wl, wl.placement, cfg.k, 3)
+        check_route_permute(g, ref, wl, cfg.k)
+        check_route_permute(run_fused(wl, wl.placement, cfg.k, 3), ref, wl, cfg.k)   # the same as one call
+        rp, rt, np_, nt, ex, tr = grace.grace_send_lists(table, 3, g.ti)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host(rp), sl.rank_send_ptr)
+        np.testing.assert_array_equal(host(rt)[:sl.rank_send_ptr[-1]], sl.rank_send_tok)
+        np.testing.assert_array_equal(host(nt)[:sl.node_send_ptr[-1]], sl.node_send_tok)
+        np.testing.assert_array_equal(host(ex), sl.expand)
+        np.testing.assert_array_equal(host(tr), sl.traffic)
+    finally:
+        grace.grace_set_fold_limits(-1, -1)
 
 
 def test_route_rr_carry_and_no_renorm():
