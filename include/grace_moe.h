@@ -62,6 +62,7 @@ typedef enum {
 #define GRACE_MAX_RANKS 1024    /* R                        */
 #define GRACE_MAX_INSTANCES 4096 /* I                       */
 #define GRACE_MAX_POLL_WEIGHT 65535u
+#define GRACE_SHARE_STATE_INTS 8 /* size of the state of grace_expert_ffn_up_share / _down_share */
 
 typedef struct grace_table grace_table; /* opaque; owns host and device copies */
 
@@ -109,15 +110,16 @@ int grace_table_instances(const grace_table *table, int32_t *inst_expert, int32_
  * experts_out must hold max_local_slots entries. */
 int grace_table_local_experts(const grace_table *table, int32_t rank, int32_t *experts_out, int32_t *n_out);
 
-/* Tuning: where the routing and permutation index kernels switch algorithm.  They turn per-chunk
- * histograms (chunks of 16 or 32 tokens in grace_route, of 512 assignments in grace_permute and
- * grace_send_lists) into prefix counts: up to one_level_max histogram loads per column of 64 keys
- * (chunks * ceil(keys / 64)) every block sums the rows before its own chunk; up to two_level_max
- * loads (of super-chunk sums of 64 rows plus the rows of the own super-chunk) it uses those
- * two-level sums, one more launch; beyond that, single-block scan kernels.  Results are identical
- * on every path.  A negative value restores the default (1024, 8192).  Process-wide; affects
- * calls made afterwards.  Always returns GRACE_OK. */
-int grace_set_fold_limits(int32_t one_level_max, int32_t two_level_max);
+/* Tuning of one table: where the routing and permutation index kernels of calls made with it switch
+ * algorithm.  They turn per-chunk histograms (chunks of 16 or 32 tokens in grace_route, of 512
+ * assignments in grace_permute and grace_send_lists) into prefix counts: up to one_level_max
+ * histogram loads per column of 64 keys (chunks * ceil(keys / 64)) every block sums the rows before
+ * its own chunk; up to two_level_max loads (of super-chunk sums of 64 rows plus the rows of the own
+ * super-chunk) it uses those two-level sums, one more launch; beyond that, single-block scan
+ * kernels.  Results are identical on every path.  A negative value restores the default (1024,
+ * 8192).  Affects calls made with this table afterwards; not to be changed while another thread
+ * is inside a call with the same table.  Errors: GRACE_EINVAL (null table). */
+int grace_table_set_fold_limits(grace_table *table, int32_t one_level_max, int32_t two_level_max);
 
 /* Bytes of device scratch that any single call below needs for these sizes
  * (the same buffer may be reused by consecutive calls on one stream).
@@ -248,6 +250,26 @@ int grace_expert_ffn_up(const grace_table *table, int32_t rank, const void *xp, 
 int grace_expert_ffn_down(const grace_table *table, int32_t rank, const int32_t *inst_off, int32_t T, int32_t k,
                           int32_t d, int32_t f, grace_dtype dt, const void *w_down, void *y, void *ws, void *stream);
 
+/* grace_expert_ffn_up / _down that also keep y a rank share from step to step.  On one GPU only
+ * the rows of `rank` are computed; the rows of other ranks, which the second all-to-all of
+ * Section 1 would deliver, are defined as zero.  The rank's row range [inst_off[first instance of
+ * rank], inst_off[last + 1]) moves with the routing, so a y buffer reused across steps would keep
+ * results of an earlier range.  Called as a pair, once each per step and in this order on one
+ * stream, _up_share records the step's range in `state` and _down_share zeroes, inside its own
+ * launch, the rows that the previous step wrote and that lie outside the current range (no extra
+ * launch, no memset, no atomics: the step stays capturable).
+ * DEVICE: state: GRACE_SHARE_STATE_INTS int32 owned by the caller, all zero before the first step
+ * (y zero-filled by the caller at that time), otherwise private to these two functions; one
+ * state per y buffer.  Rows are cleared with 16-byte stores: d * sizeof(dt) must be a multiple of
+ * 16.  When `rank` hosts no instance nothing is launched and y is never written.  Other arguments
+ * as for grace_expert_ffn_up / grace_expert_ffn_down. */
+int grace_expert_ffn_up_share(const grace_table *table, int32_t rank, const void *xp, const int32_t *inst_off, int32_t T,
+                              int32_t k, int32_t d, int32_t f, grace_dtype dt, const void *w_gate, const void *w_up,
+                              int32_t *state, void *ws, void *stream);
+int grace_expert_ffn_down_share(const grace_table *table, int32_t rank, const int32_t *inst_off, int32_t T, int32_t k,
+                                int32_t d, int32_t f, grace_dtype dt, const void *w_down, void *y, int32_t *state,
+                                void *ws, void *stream);
+
 /* Always-on shared experts evaluated on all T token rows and summed:
  *     y_shared[t] = sum_s W_down[s] ( silu(W_gate[s] x[t]) * (W_up[s] x[t]) ).
  * DEVICE: x [T,d]; w_gate, w_up [n_shared,f,d]; w_down [n_shared,d,f];
@@ -255,6 +277,14 @@ int grace_expert_ffn_down(const grace_table *table, int32_t rank, const int32_t 
 int grace_shared_ffn(const void *x, int32_t T, int32_t d, int32_t f, int32_t n_shared, grace_dtype dt,
                      const void *w_gate, const void *w_up, const void *w_down, void *y_shared, void *ws,
                      void *stream);
+
+/* The two launches of grace_shared_ffn as separate calls (as for grace_expert_ffn): _up writes the
+ * hidden activation of all T rows to ws ([T, n_shared*f] of dt), _down reads it and writes
+ * y_shared.  grace_shared_ffn(...) == _up(...) then _down(...) with the same ws. */
+int grace_shared_ffn_up(const void *x, int32_t T, int32_t d, int32_t f, int32_t n_shared, grace_dtype dt,
+                        const void *w_gate, const void *w_up, void *ws, void *stream);
+int grace_shared_ffn_down(int32_t T, int32_t d, int32_t f, int32_t n_shared, grace_dtype dt, const void *w_down,
+                          void *y_shared, void *ws, void *stream);
 
 /* ---- grace_combine: weighted aggregation back to token order ----------------
  * The aggregation step that follows the expert computation (Section 1):
@@ -271,8 +301,10 @@ int grace_combine(const void *y, const int32_t *perm_pos, const float *topk_weig
  * inner instruction mix and no global traffic (8 wavefronts per CU, one barrier
  * per 32 MFMAs): constant or pseudo-random operands (a power-limited part runs
  * slower the more operand bits toggle), fragments held in registers or re-read
- * from LDS.  Allocates a small device buffer, runs for a few tens of
- * milliseconds on `stream` and synchronises it.  HOST output: TFLOP/s. */
+ * from LDS.  NOT for the hot path and the one exception to the conventions
+ * above: it allocates and frees a small device buffer (hipMalloc / hipFree),
+ * runs for a few tens of milliseconds on `stream` and synchronises it, so it
+ * must not be called under stream capture.  HOST output: TFLOP/s. */
 int grace_mfma_sustained(int32_t random_operands, int32_t lds_fed, double *tflops_out, void *stream);
 
 /* Text of the calling thread's most recent error ("" if none).  The pointer

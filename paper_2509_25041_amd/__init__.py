@@ -17,14 +17,15 @@ from .binding import (  # noqa: F401
     grace_combine,
     grace_expert_ffn,
     grace_expert_ffn_down,
+    grace_expert_ffn_down_share,
     grace_expert_ffn_up,
+    grace_expert_ffn_up_share,
     grace_last_error,
     grace_mfma_sustained,
     grace_permute,
     grace_route,
     grace_route_permute,
     grace_send_lists,
-    grace_set_fold_limits,
     grace_shared_ffn,
     grace_table_validate,
     grace_workspace_bytes,

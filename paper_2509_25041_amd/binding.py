@@ -12,13 +12,17 @@ from . import build as _build
 
 GRACE_F32, GRACE_BF16 = 0, 1
 GRACE_POLICY_TAR, GRACE_POLICY_WRR = 0, 1
+SHARE_STATE_INTS = 8      # GRACE_SHARE_STATE_INTS
 _STATUS = {0: "GRACE_OK", -1: "GRACE_EINVAL", -2: "GRACE_ESHAPE", -3: "GRACE_ETABLE", -4: "GRACE_ENOMEM",
            -5: "GRACE_EHIP"}
 
 EXPORTS = ("grace_table_validate", "grace_table_create", "grace_table_destroy", "grace_table_info",
-           "grace_table_instances", "grace_table_local_experts", "grace_set_fold_limits", "grace_workspace_bytes", "grace_route",
+           "grace_table_instances", "grace_table_local_experts", "grace_table_set_fold_limits", "grace_workspace_bytes",
+           "grace_route",
            "grace_permute", "grace_route_permute", "grace_send_lists", "grace_expert_ffn", "grace_expert_ffn_up",
-           "grace_expert_ffn_down", "grace_shared_ffn", "grace_combine", "grace_mfma_sustained", "grace_last_error")
+           "grace_expert_ffn_down", "grace_expert_ffn_up_share", "grace_expert_ffn_down_share",
+           "grace_shared_ffn", "grace_shared_ffn_up", "grace_shared_ffn_down", "grace_combine", "grace_mfma_sustained",
+           "grace_last_error")
 
 _lib: Optional[C.CDLL] = None
 
@@ -34,11 +38,13 @@ def library_path() -> str:
 
 
 def load_library() -> C.CDLL:
-    """Load the in-tree shared library (built first if it is absent)."""
+    """Load the in-tree shared library.  It is built first when it is absent or older than any of
+    its sources, so a forgotten rebuild cannot put yesterday's kernels under today's tests; where the
+    sources are newer and no compiler is available the call fails instead of loading the old code."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB):
+    if _build.is_stale():
         _build.build()
     lib = C.CDLL(_build.LIB)
     vp, i32, u64 = C.c_void_p, C.c_int32, C.c_size_t
@@ -50,7 +56,7 @@ def load_library() -> C.CDLL:
     lib.grace_table_info.argtypes = [vp] + [C.POINTER(i32)] * 5
     lib.grace_table_instances.argtypes = [vp, vp, vp, vp]
     lib.grace_table_local_experts.argtypes = [vp, i32, vp, C.POINTER(i32)]
-    lib.grace_set_fold_limits.argtypes = [i32, i32]
+    lib.grace_table_set_fold_limits.argtypes = [vp, i32, i32]
     lib.grace_workspace_bytes.restype = u64
     lib.grace_workspace_bytes.argtypes = [i32] * 7 + [C.c_int]
     lib.grace_route.argtypes = [vp, i32, C.c_int, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -61,7 +67,11 @@ def load_library() -> C.CDLL:
     lib.grace_expert_ffn.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp, vp]
     lib.grace_expert_ffn_up.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp]
     lib.grace_expert_ffn_down.argtypes = [vp, i32, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp]
+    lib.grace_expert_ffn_up_share.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp]
+    lib.grace_expert_ffn_down_share.argtypes = [vp, i32, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp]
     lib.grace_shared_ffn.argtypes = [vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp, vp]
+    lib.grace_shared_ffn_up.argtypes = [vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp]
+    lib.grace_shared_ffn_down.argtypes = [i32, i32, i32, i32, C.c_int, vp, vp, vp, vp]
     lib.grace_combine.argtypes = [vp, vp, vp, i32, i32, i32, C.c_int, vp, vp, vp]
     lib.grace_mfma_sustained.argtypes = [i32, i32, C.POINTER(C.c_double), vp]
     for name in EXPORTS:
@@ -115,11 +125,6 @@ def grace_table_validate(E, R, N, rank_node, poll_weight, inst_ptr, inst_rank) -
     _check(load_library().grace_table_validate(E, R, N, *[_hp(x) for x in a]))
 
 
-def grace_set_fold_limits(one_level_max: int = -1, two_level_max: int = -1) -> None:
-    """Switch points of the index kernels' prefix-count algorithms (negative: defaults); see grace_moe.h."""
-    _check(load_library().grace_set_fold_limits(one_level_max, two_level_max))
-
-
 def grace_workspace_bytes(T, E, k, I, d=0, f=0, n_shared=0, dt=GRACE_BF16) -> int:
     return int(load_library().grace_workspace_bytes(T, E, k, I, d, f, n_shared, dt))
 
@@ -159,6 +164,11 @@ class GraceTable:
         n = C.c_int32()
         _check(load_library().grace_table_local_experts(self.handle, rank, _hp(buf), C.byref(n)))
         return buf[:n.value].copy()
+
+    def set_fold_limits(self, one_level_max: int = -1, two_level_max: int = -1) -> None:
+        """Switch points of the index kernels' prefix-count algorithms for calls with this table
+        (negative: defaults); see grace_moe.h."""
+        _check(load_library().grace_table_set_fold_limits(self.handle, one_level_max, two_level_max))
 
     def destroy(self) -> None:
         if getattr(self, "_h", None) is not None:
@@ -295,6 +305,30 @@ def grace_expert_ffn_down(table: GraceTable, rank: int, inst_off: torch.Tensor, 
     S, d, f = w_down.shape
     _check(load_library().grace_expert_ffn_down(table.handle, rank, _dp(inst_off), T, k, d, f, _dtype_code(y),
                                                 _dp(w_down) if S else None, _dp(y), _dp(ws), _stream()))
+
+
+def grace_expert_ffn_up_share(table: GraceTable, rank: int, xp: torch.Tensor, inst_off: torch.Tensor, T: int, k: int,
+                              w_gate: torch.Tensor, w_up: torch.Tensor, state: torch.Tensor, ws: torch.Tensor) -> None:
+    """grace_expert_ffn_up that also records the rank's row range of this step in `state` (first half of
+    the pair with grace_expert_ffn_down_share); see grace_moe.h."""
+    if state.dtype != torch.int32 or state.numel() < SHARE_STATE_INTS:
+        raise ValueError(f"state must hold {SHARE_STATE_INTS} int32")
+    S, f, d = w_gate.shape
+    _check(load_library().grace_expert_ffn_up_share(table.handle, rank, _dp(xp), _dp(inst_off), T, k, d, f, _dtype_code(xp),
+                                                    _dp(w_gate) if S else None, _dp(w_up) if S else None, _dp(state),
+                                                    _dp(ws), _stream()))
+
+
+def grace_expert_ffn_down_share(table: GraceTable, rank: int, inst_off: torch.Tensor, T: int, k: int, w_down: torch.Tensor,
+                                y: torch.Tensor, state: torch.Tensor, ws: torch.Tensor) -> None:
+    """grace_expert_ffn_down that also zeroes the rows the previous step (same `state`: SHARE_STATE_INTS
+    int32 on the device, zero before the first step, kept by grace_expert_ffn_up_share) wrote outside the
+    rank's current row range; see grace_moe.h."""
+    if state.dtype != torch.int32 or state.numel() < SHARE_STATE_INTS:
+        raise ValueError(f"state must hold {SHARE_STATE_INTS} int32")
+    S, d, f = w_down.shape
+    _check(load_library().grace_expert_ffn_down_share(table.handle, rank, _dp(inst_off), T, k, d, f, _dtype_code(y),
+                                                      _dp(w_down) if S else None, _dp(y), _dp(state), _dp(ws), _stream()))
 
 
 def grace_shared_ffn(x: torch.Tensor, w_gate: torch.Tensor, w_up: torch.Tensor, w_down: torch.Tensor,

@@ -1,6 +1,7 @@
 """Builds libgrace_moe.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree."""
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 import sys
@@ -13,14 +14,28 @@ SOURCES = ["table.cpp", "route.hip", "permute.hip", "combine.hip", "ffn.hip", "c
            "route_permute_small.hip"]
 
 
-def _newest_source_mtime() -> float:
-    paths = [os.path.join(CSRC, n) for n in os.listdir(CSRC)]
+STAMP = os.path.join(HERE, "libgrace_moe.stamp")   # digest of the sources the library was built from
+
+
+def source_digest() -> str:
+    """SHA-256 over the names and contents of every file the library is compiled from (content, not
+    modification times: a copy of the tree to another machine keeps the answer)."""
+    paths = sorted(os.path.join(CSRC, n) for n in os.listdir(CSRC) if n.endswith((".hip", ".h", ".cpp")))
     paths.append(os.path.join(ROOT, "include", "grace_moe.h"))
-    return max(os.path.getmtime(p) for p in paths)
+    h = hashlib.sha256()
+    for p in paths:
+        h.update(os.path.basename(p).encode() + b"\0")
+        with open(p, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
 
 
 def is_stale() -> bool:
-    return not os.path.exists(LIB) or os.path.getmtime(LIB) < _newest_source_mtime()
+    """True when the library is absent or was built from other sources than the ones in the tree."""
+    if not os.path.exists(LIB) or not os.path.exists(STAMP):
+        return True
+    with open(STAMP) as fh:
+        return fh.read().strip() != source_digest()
 
 
 def build(verbose: bool = False) -> str:
@@ -50,8 +65,11 @@ def build(verbose: bool = False) -> str:
             print(out)
     if failed:
         raise RuntimeError("hipcc failed")
+    digest = source_digest()
     link = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     subprocess.run(link, check=True)
+    with open(STAMP, "w") as fh:
+        fh.write(digest + "\n")
     return LIB
 
 

@@ -9,6 +9,8 @@
 
 #include "grace_moe.h"
 
+struct grace_table;
+
 namespace grace {
 
 // Thread-local error text behind grace_last_error().
@@ -41,12 +43,12 @@ constexpr int PERM_CHUNK = 512;              // permute: chunk = 512 assignments
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// How the index kernels turn chunk histograms into prefix counts (grace_set_fold_limits moves the
-// switch points).  0: separate single-block scan kernels; 1: every block sums the rows before its
+// How the index kernels turn chunk histograms into prefix counts (grace_table_set_fold_limits moves
+// a table's switch points).  0: separate single-block scan kernels; 1: every block sums the rows before its
 // chunk; 2: two-level sums (super-chunks of 64 rows, one extra launch).
 constexpr int FOLD_ONE_LEVEL_DEFAULT = 1024;  // histogram loads per key column a block may spend on a one-level sum
 constexpr int FOLD_TWO_LEVEL_DEFAULT = 8192;  // the same for the super rows + chunk rows of a two-level sum
-int fold_mode(int nchunks, int nkeys);
+int fold_mode(const grace_table *table, int nchunks, int nkeys);
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace grace
@@ -97,4 +99,6 @@ struct grace_table {
     const int32_t *d_node_first_inst = nullptr;  // [N+1] first instance id of each node (I at the end)
     const int32_t *d_inst_rank = nullptr;        // [I] hosting rank of each instance id
     const int32_t *d_rank_node = nullptr;        // [R]
+    // switch points of the index kernels' prefix-count algorithms for calls with this table
+    int fold_one_level = grace::FOLD_ONE_LEVEL_DEFAULT, fold_two_level = grace::FOLD_TWO_LEVEL_DEFAULT;
 };

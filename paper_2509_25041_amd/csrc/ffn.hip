@@ -36,7 +36,7 @@ static int compute_units() {
 
 // The persistent kernel needs the 160 KB of dynamic LDS opted in, once per kernel and device.
 static bool allow_full_lds(const void *kernel, const char *what) {
-    constexpr int MAX_KERNELS = 4, MAX_DEVICES = 64;
+    constexpr int MAX_KERNELS = 8, MAX_DEVICES = 64;
     static std::mutex mu;
     static const void *known[MAX_KERNELS] = {nullptr};
     static bool done[MAX_KERNELS][MAX_DEVICES] = {{false}};
@@ -64,7 +64,7 @@ static bool allow_full_lds(const void *kernel, const char *what) {
     return true;
 }
 
-template <bool FUSED_UP>
+template <bool FUSED_UP, pers::Who WHO>
 static int launch_gemm(const GemmArgs &g, grace_dtype dt, int64_t m_bound, hipStream_t st, const char *what) {
     if (m_bound <= 0 || g.N <= 0 || g.K <= 0) return GRACE_OK;
     const int n_seg = g.seg_off ? g.S : 1;
@@ -79,11 +79,11 @@ static int launch_gemm(const GemmArgs &g, grace_dtype dt, int64_t m_bound, hipSt
         const int grid = pers::grid_blocks(n_cu);
         if ((m_bound / pers::BM + n_seg) * (int64_t)ntn > INT32_MAX) return fail(GRACE_ESHAPE, "%s: too many tiles", what);
         if (n_seg <= 64) {
-            if (!allow_full_lds((const void *)pers::gemm_bf16_persist_kernel<FUSED_UP, 1>, what)) return GRACE_EHIP;
-            pers::gemm_bf16_persist_kernel<FUSED_UP, 1><<<grid, pers::THREADS, pers::LDS_BYTES, st>>>(g, ntn);
-        } else {
-            if (!allow_full_lds((const void *)pers::gemm_bf16_persist_kernel<FUSED_UP, 4>, what)) return GRACE_EHIP;
-            pers::gemm_bf16_persist_kernel<FUSED_UP, 4><<<grid, pers::THREADS, pers::LDS_BYTES, st>>>(g, ntn);
+            if (!allow_full_lds((const void *)pers::gemm_bf16_persist_kernel<FUSED_UP, 1, WHO>, what)) return GRACE_EHIP;
+            pers::gemm_bf16_persist_kernel<FUSED_UP, 1, WHO><<<grid, pers::THREADS, pers::LDS_BYTES, st>>>(g, ntn);
+        } else if constexpr (WHO == pers::EXPERTS) {  // the shared experts are a single row segment
+            if (!allow_full_lds((const void *)pers::gemm_bf16_persist_kernel<FUSED_UP, 4, WHO>, what)) return GRACE_EHIP;
+            pers::gemm_bf16_persist_kernel<FUSED_UP, 4, WHO><<<grid, pers::THREADS, pers::LDS_BYTES, st>>>(g, ntn);
         }
     } else if (dt == GRACE_BF16) {
         constexpr int BN = FUSED_UP ? 64 : 128;
@@ -126,42 +126,75 @@ static int expert_ffn_common(const char *who, const grace_table *table, int32_t 
     return GRACE_OK;
 }
 
-extern "C" int grace_expert_ffn_up(const grace_table *table, int32_t rank, const void *xp, const int32_t *inst_off,
-                                   int32_t T, int32_t k, int32_t d, int32_t f, grace_dtype dt, const void *w_gate,
-                                   const void *w_up, void *ws, void *stream) {
+static int expert_ffn_up(const char *who, const grace_table *table, int32_t rank, const void *xp, const int32_t *inst_off,
+                         int32_t T, int32_t k, int32_t d, int32_t f, grace_dtype dt, const void *w_gate, const void *w_up,
+                         int32_t *state, void *ws, void *stream) {
     int g0, S;
-    int rc = expert_ffn_common("expert_ffn_up", table, rank, T, k, d, f, dt, g0, S);
+    int rc = expert_ffn_common(who, table, rank, T, k, d, f, dt, g0, S);
     if (rc != GRACE_OK) return rc;
     if (S == 0 || T == 0) return GRACE_OK;
-    if (!xp || !inst_off || !w_gate || !w_up || !ws) return fail(GRACE_EINVAL, "expert_ffn_up: null device pointer");
+    if (!xp || !inst_off || !w_gate || !w_up || !ws) return fail(GRACE_EINVAL, "%s: null device pointer", who);
     if ((((uintptr_t)xp) | ((uintptr_t)w_gate) | ((uintptr_t)w_up) | ((uintptr_t)ws)) & 15)
-        return fail(GRACE_EINVAL, "expert_ffn_up: device pointers must be 16-byte aligned");
+        return fail(GRACE_EINVAL, "%s: device pointers must be 16-byte aligned", who);
     GemmArgs up{};
     up.A = xp; up.lda = d;
     up.B0 = w_gate; up.B1 = w_up; up.b_slot_stride = (int64_t)d * f; up.ldb = d;
     up.N = f; up.K = d; up.kseg_len = d; up.kseg_stride = 0;
     up.out = ws; up.ldo = f;
     up.seg_off = inst_off + g0; up.S = S; up.M_single = 0;
-    return launch_gemm<true>(up, dt, (int64_t)T * k, (hipStream_t)stream, "expert_ffn up projection");
+    up.share_state = state;
+    return launch_gemm<true, pers::EXPERTS>(up, dt, (int64_t)T * k, (hipStream_t)stream, who);
 }
 
-extern "C" int grace_expert_ffn_down(const grace_table *table, int32_t rank, const int32_t *inst_off, int32_t T,
-                                     int32_t k, int32_t d, int32_t f, grace_dtype dt, const void *w_down, void *y,
-                                     void *ws, void *stream) {
+extern "C" int grace_expert_ffn_up(const grace_table *table, int32_t rank, const void *xp, const int32_t *inst_off,
+                                   int32_t T, int32_t k, int32_t d, int32_t f, grace_dtype dt, const void *w_gate,
+                                   const void *w_up, void *ws, void *stream) {
+    return expert_ffn_up("expert_ffn_up", table, rank, xp, inst_off, T, k, d, f, dt, w_gate, w_up, nullptr, ws, stream);
+}
+
+extern "C" int grace_expert_ffn_up_share(const grace_table *table, int32_t rank, const void *xp, const int32_t *inst_off,
+                                         int32_t T, int32_t k, int32_t d, int32_t f, grace_dtype dt, const void *w_gate,
+                                         const void *w_up, int32_t *state, void *ws, void *stream) {
+    if (!state) return fail(GRACE_EINVAL, "expert_ffn_up_share: state is null");
+    return expert_ffn_up("expert_ffn_up_share", table, rank, xp, inst_off, T, k, d, f, dt, w_gate, w_up, state, ws, stream);
+}
+
+static_assert(SHARE_STATE_INTS == GRACE_SHARE_STATE_INTS, "header and kernels must agree on the state size");
+
+static int expert_ffn_down(const char *who, const grace_table *table, int32_t rank, const int32_t *inst_off, int32_t T,
+                           int32_t k, int32_t d, int32_t f, grace_dtype dt, const void *w_down, void *y, int32_t *state,
+                           void *ws, void *stream) {
     int g0, S;
-    int rc = expert_ffn_common("expert_ffn_down", table, rank, T, k, d, f, dt, g0, S);
+    int rc = expert_ffn_common(who, table, rank, T, k, d, f, dt, g0, S);
     if (rc != GRACE_OK) return rc;
     if (S == 0 || T == 0) return GRACE_OK;
-    if (!inst_off || !w_down || !y || !ws) return fail(GRACE_EINVAL, "expert_ffn_down: null device pointer");
+    if (!inst_off || !w_down || !y || !ws) return fail(GRACE_EINVAL, "%s: null device pointer", who);
     if ((((uintptr_t)w_down) | ((uintptr_t)y) | ((uintptr_t)ws)) & 15)
-        return fail(GRACE_EINVAL, "expert_ffn_down: device pointers must be 16-byte aligned");
+        return fail(GRACE_EINVAL, "%s: device pointers must be 16-byte aligned", who);
+    const size_t el = dt == GRACE_F32 ? 4 : 2;
+    if (state && ((size_t)d * el) % 16 != 0)
+        return fail(GRACE_ESHAPE, "%s: row of %zu bytes is not a multiple of 16", who, (size_t)d * el);
     GemmArgs dn{};
     dn.A = ws; dn.lda = f;
     dn.B0 = w_down; dn.B1 = nullptr; dn.b_slot_stride = (int64_t)d * f; dn.ldb = f;
     dn.N = d; dn.K = f; dn.kseg_len = f; dn.kseg_stride = 0;
     dn.out = y; dn.ldo = d;
     dn.seg_off = inst_off + g0; dn.S = S; dn.M_single = 0;
-    return launch_gemm<false>(dn, dt, (int64_t)T * k, (hipStream_t)stream, "expert_ffn down projection");
+    dn.share_state = state; dn.share_rows = (int64_t)T * k; dn.share_row_vec = (int)((size_t)d * el / 16);
+    return launch_gemm<false, pers::EXPERTS>(dn, dt, (int64_t)T * k, (hipStream_t)stream, who);
+}
+
+extern "C" int grace_expert_ffn_down(const grace_table *table, int32_t rank, const int32_t *inst_off, int32_t T,
+                                     int32_t k, int32_t d, int32_t f, grace_dtype dt, const void *w_down, void *y,
+                                     void *ws, void *stream) {
+    return expert_ffn_down("expert_ffn_down", table, rank, inst_off, T, k, d, f, dt, w_down, y, nullptr, ws, stream);
+}
+
+extern "C" int grace_expert_ffn_down_share(const grace_table *table, int32_t rank, const int32_t *inst_off, int32_t T,
+                                           int32_t k, int32_t d, int32_t f, grace_dtype dt, const void *w_down, void *y,
+                                           int32_t *state, void *ws, void *stream) {
+    if (!state) return fail(GRACE_EINVAL, "expert_ffn_down_share: state is null");
+    return expert_ffn_down("expert_ffn_down_share", table, rank, inst_off, T, k, d, f, dt, w_down, y, state, ws, stream);
 }
 
 extern "C" int grace_expert_ffn(const grace_table *table, int32_t rank, const void *xp, const int32_t *inst_off,
@@ -172,33 +205,61 @@ extern "C" int grace_expert_ffn(const grace_table *table, int32_t rank, const vo
     return grace_expert_ffn_down(table, rank, inst_off, T, k, d, f, dt, w_down, y, ws, stream);
 }
 
-extern "C" int grace_shared_ffn(const void *x, int32_t T, int32_t d, int32_t f, int32_t n_shared, grace_dtype dt,
-                                const void *w_gate, const void *w_up, const void *w_down, void *y_shared, void *ws,
-                                void *stream) {
-    if (T < 0 || n_shared < 1) return fail(GRACE_EINVAL, "shared_ffn: T=%d, n_shared=%d invalid", T, n_shared);
-    int rc = check_ffn_shapes("shared_ffn", d, f, dt);
+static int shared_ffn_common(const char *who, int32_t T, int32_t d, int32_t f, int32_t n_shared, grace_dtype dt) {
+    if (T < 0 || n_shared < 1) return fail(GRACE_EINVAL, "%s: T=%d, n_shared=%d invalid", who, T, n_shared);
+    int rc = check_ffn_shapes(who, d, f, dt);
     if (rc != GRACE_OK) return rc;
-    if ((int64_t)n_shared * f > INT32_MAX) return fail(GRACE_ESHAPE, "shared_ffn: n_shared*f too large");
+    if ((int64_t)n_shared * f > INT32_MAX) return fail(GRACE_ESHAPE, "%s: n_shared*f too large", who);
+    return GRACE_OK;
+}
+
+// The shared experts act as one expert of width F = n_shared * f: gate and up weights [n_shared, f, d]
+// are one [F, d] matrix each; the down weights [n_shared, d, f] are F input features in n_shared
+// K segments of length f that lie d * f elements apart.
+extern "C" int grace_shared_ffn_up(const void *x, int32_t T, int32_t d, int32_t f, int32_t n_shared, grace_dtype dt,
+                                   const void *w_gate, const void *w_up, void *ws, void *stream) {
+    int rc = shared_ffn_common("shared_ffn_up", T, d, f, n_shared, dt);
+    if (rc != GRACE_OK) return rc;
     if (T == 0) return GRACE_OK;
-    if (!x || !w_gate || !w_up || !w_down || !y_shared || !ws) return fail(GRACE_EINVAL, "shared_ffn: null device pointer");
-    if ((((uintptr_t)x) | ((uintptr_t)w_gate) | ((uintptr_t)w_up) | ((uintptr_t)w_down) | ((uintptr_t)y_shared) |
-         ((uintptr_t)ws)) & 15)
-        return fail(GRACE_EINVAL, "shared_ffn: device pointers must be 16-byte aligned");
-    hipStream_t st = (hipStream_t)stream;
-    const int F = n_shared * f;  // the shared experts act as one expert of width n_shared * f
+    if (!x || !w_gate || !w_up || !ws) return fail(GRACE_EINVAL, "shared_ffn_up: null device pointer");
+    if ((((uintptr_t)x) | ((uintptr_t)w_gate) | ((uintptr_t)w_up) | ((uintptr_t)ws)) & 15)
+        return fail(GRACE_EINVAL, "shared_ffn_up: device pointers must be 16-byte aligned");
+    const int F = n_shared * f;
     GemmArgs up{};
     up.A = x; up.lda = d;
-    up.B0 = w_gate; up.B1 = w_up; up.b_slot_stride = 0; up.ldb = d;   // [n_shared, f, d] viewed as [F, d]
+    up.B0 = w_gate; up.B1 = w_up; up.b_slot_stride = 0; up.ldb = d;
     up.N = F; up.K = d; up.kseg_len = d; up.kseg_stride = 0;
     up.out = ws; up.ldo = F;
     up.seg_off = nullptr; up.S = 1; up.M_single = T;
-    rc = launch_gemm<true>(up, dt, T, st, "shared_ffn up projection");
+    return launch_gemm<true, pers::SHARED>(up, dt, T, (hipStream_t)stream, "shared_ffn up projection");
+}
+
+extern "C" int grace_shared_ffn_down(int32_t T, int32_t d, int32_t f, int32_t n_shared, grace_dtype dt,
+                                     const void *w_down, void *y_shared, void *ws, void *stream) {
+    int rc = shared_ffn_common("shared_ffn_down", T, d, f, n_shared, dt);
     if (rc != GRACE_OK) return rc;
+    if (T == 0) return GRACE_OK;
+    if (!w_down || !y_shared || !ws) return fail(GRACE_EINVAL, "shared_ffn_down: null device pointer");
+    if ((((uintptr_t)w_down) | ((uintptr_t)y_shared) | ((uintptr_t)ws)) & 15)
+        return fail(GRACE_EINVAL, "shared_ffn_down: device pointers must be 16-byte aligned");
+    const int F = n_shared * f;
     GemmArgs dn{};
     dn.A = ws; dn.lda = F;
     dn.B0 = w_down; dn.B1 = nullptr; dn.b_slot_stride = 0; dn.ldb = f;
     dn.N = d; dn.K = F; dn.kseg_len = f; dn.kseg_stride = (int64_t)d * f;  // K segment s lives in w_down[s]
     dn.out = y_shared; dn.ldo = d;
     dn.seg_off = nullptr; dn.S = 1; dn.M_single = T;
-    return launch_gemm<false>(dn, dt, T, st, "shared_ffn down projection");
+    return launch_gemm<false, pers::SHARED>(dn, dt, T, (hipStream_t)stream, "shared_ffn down projection");
+}
+
+extern "C" int grace_shared_ffn(const void *x, int32_t T, int32_t d, int32_t f, int32_t n_shared, grace_dtype dt,
+                                const void *w_gate, const void *w_up, const void *w_down, void *y_shared, void *ws,
+                                void *stream) {
+    int rc = shared_ffn_common("shared_ffn", T, d, f, n_shared, dt);
+    if (rc != GRACE_OK) return rc;
+    if (T == 0) return GRACE_OK;
+    if (!w_down || !y_shared) return fail(GRACE_EINVAL, "shared_ffn: null device pointer");
+    rc = grace_shared_ffn_up(x, T, d, f, n_shared, dt, w_gate, w_up, ws, stream);
+    if (rc != GRACE_OK) return rc;
+    return grace_shared_ffn_down(T, d, f, n_shared, dt, w_down, y_shared, ws, stream);
 }

@@ -26,6 +26,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g, int n_
     const int wm = wave >> 1, wn = wave & 1;
     const int nt = (int)blockIdx.x % n_tiles_n, mt = (int)blockIdx.x / n_tiles_n;
     int slot, m0, m_end;
+    if (FUSED_UP) share_record(g); else share_clear_stale(g);
     if (!locate_tile<BM>(g, mt, slot, m0, m_end)) return;
     const int n0 = nt * BN;
     const uint16_t *A = (const uint16_t *)g.A;

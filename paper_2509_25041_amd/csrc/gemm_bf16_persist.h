@@ -90,8 +90,11 @@ __device__ __forceinline__ void load16_to_lds(const char *base, uint32_t voff, c
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0" ::"s"(base), "v"(voff), "s"(lds_addr) : "memory");
 }
 
-// SEG_PER_LANE: 1 for up to 64 row segments, 4 for up to 256.
-template <bool FUSED_UP, int SEG_PER_LANE>
+// SEG_PER_LANE: 1 for up to 64 row segments, 4 for up to 256.  WHO only names the instantiation
+// (EXPERTS: grouped expert FFN, SHARED: always-on shared experts), so that a kernel trace lists the
+// two uses separately.
+enum Who { EXPERTS = 0, SHARED = 1 };
+template <bool FUSED_UP, int SEG_PER_LANE, Who WHO>
 __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const GemmArgs g, int n_tiles_n) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     using SH = Shape<FUSED_UP>;
@@ -133,6 +136,10 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
         const int q = j_first + job;
         return (flat ? (m_fastest ? q / total_mt : q % n_tiles_n) : job % n_tiles_n) * BN;
     };
+    // rank-share upkeep of the expert down projection's output (no-op unless the launcher asks for it)
+    if (WHO == EXPERTS) {
+        if (FUSED_UP) share_record(g); else share_clear_stale(g);
+    }
     int job = bslot;
     if (job >= njobs) return;
 

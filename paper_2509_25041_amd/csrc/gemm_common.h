@@ -21,7 +21,47 @@ struct GemmArgs {
     const int32_t *seg_off; // device: S+1 row offsets of the local slots, or null
     int S;
     int M_single;           // rows of the single segment when seg_off is null
+    // Rank-share upkeep of the down projection's output buffer (null: off).  share_state: [0], [1] =
+    // first and end row that the previous step wrote, [4], [5] = the same for the current step.  The up
+    // projection's launch keeps the record, the down projection's launch (a later kernel on the same
+    // stream) only reads it: no kernel reads what another workgroup of the same launch writes.
+    int32_t *share_state;
+    int64_t share_rows;     // rows of the whole output buffer
+    int share_row_vec;      // 16-byte vectors per output row
 };
+constexpr int SHARE_STATE_INTS = 8;
+
+// Up projection, first thread of the grid: what was the current range becomes the previous one, the
+// segments of this step the current one.
+__device__ __forceinline__ void share_record(const GemmArgs &g) {
+    if (!g.share_state || blockIdx.x != 0 || threadIdx.x != 0) return;
+    const int32_t p0 = g.share_state[4], p1 = g.share_state[5];
+    g.share_state[0] = p0;
+    g.share_state[1] = p1;
+    g.share_state[4] = g.seg_off[0];
+    g.share_state[5] = g.seg_off[g.S];
+}
+
+// Down projection: rows of the output that the previous step wrote for this rank and the current
+// segments no longer cover would keep old results; every workgroup zeroes its part of them before
+// it does anything else (they lie outside the rows this launch writes).
+__device__ __forceinline__ void share_clear_stale(const GemmArgs &g) {
+    if (!g.share_state) return;
+    const int64_t n = g.share_rows;
+    const int64_t pl = max((int64_t)0, min(n, (int64_t)g.share_state[0]));
+    const int64_t ph = max(pl, min(n, (int64_t)g.share_state[1]));
+    const int64_t nl = max((int64_t)0, min(n, (int64_t)g.seg_off[0]));
+    const int64_t nh = max(nl, min(n, (int64_t)g.seg_off[g.S]));
+    // stale rows: [pl, min(ph, nl)) and [max(pl, nh), ph)
+    const int64_t a_end = max(pl, min(ph, nl)), b_begin = min(ph, max(pl, nh));
+    const int64_t n_a = (a_end - pl) * g.share_row_vec, n_b = (ph - b_begin) * g.share_row_vec;
+    uint4 *y = (uint4 *)g.out;
+    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_a + n_b; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t v = i < n_a ? pl * g.share_row_vec + i : b_begin * g.share_row_vec + (i - n_a);
+        y[v] = zero;
+    }
+}
 
 // Which (slot, row range) does m-tile `mt` fall into?  Returns false for surplus tiles.
 template <int BM>

@@ -18,6 +18,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g, int n_t
     const int tx = tid & 15, ty = tid >> 4;
     const int nt = (int)blockIdx.x % n_tiles_n, mt = (int)blockIdx.x / n_tiles_n;
     int slot, m0, m_end;
+    if (FUSED_UP) share_record(g); else share_clear_stale(g);
     if (!locate_tile<FBM>(g, mt, slot, m0, m_end)) return;
     const int n0 = nt * FBN;
     const float *A = (const float *)g.A;

@@ -78,7 +78,7 @@ extern "C" int grace_permute(const grace_table *table, const int32_t *topk_inst,
     const int nchunks = (int)ceil_div(n, PERM_CHUNK);
     int32_t *hist = (int32_t *)ws;
     int32_t *base = (int32_t *)((char *)ws + align_up((size_t)nchunks * I * 4, 256));
-    const char *failed = stable_sort_launch(topk_inst, n, I, 1, hist, base, table->R, table->N, table->d_rank_ptr,
+    const char *failed = stable_sort_launch(table, topk_inst, n, I, 1, hist, base, table->R, table->N, table->d_rank_ptr,
                                             table->d_node_first_inst, inst_off, rank_off, node_off, perm_pos, perm_src, st);
     if (failed) return fail(GRACE_EHIP, "permute: launch of %s failed", failed);
     if (nchunks > 0 && x) return launch_scatter_rows(x, T, k, d, dt, perm_pos, xp, st);

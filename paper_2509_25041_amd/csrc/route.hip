@@ -167,7 +167,8 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
     }
     if (wave != 0) return;
     // One wavefront walks the chunk in order.  Its LDS operations execute in program order, so a
-    // counter updated by the last lane of a match set is seen by the next group of 64 assignments.
+    // counter updated by the last lane of a match set is seen by the next group of 64 assignments
+    // (wave_ctr_* accesses, fenced per round).
     const int32_t *t_ptr = table_in_lds ? s_ptr : cand_ptr;
     const int32_t *t_g = table_in_lds ? s_g : cand_g;
     const uint32_t *t_cum = table_in_lds ? s_cum : cand_cum;
@@ -184,12 +185,13 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
             const uint64_t same = wave_match((uint32_t)e, valid, nbits);
             if (valid) {
                 const uint32_t rank = (uint32_t)__popcll(same & lt);
-                const uint64_t c = (uint64_t)cnt[e] + rank + (uint64_t)(rr_in ? rr_in[e] : 0u);
+                const uint64_t c = (uint64_t)wave_ctr_load(&cnt[e]) + rank + (uint64_t)(rr_in ? rr_in[e] : 0u);
                 const int g = pick_candidate(c, e, t_ptr, t_g, t_cum);
                 topk_inst[a] = g;
                 if (inst_hist && (unsigned)g < (unsigned)I) atomicAdd(&inst_hist[(a / PERM_CHUNK) * I + g], 1);
             }
-            if (valid && is_last_of(same)) cnt[e] += (uint32_t)__popcll(same);
+            if (valid && is_last_of(same)) wave_ctr_add(&cnt[e], (uint32_t)__popcll(same));
+            wave_ctr_fence();
         }
     }
 }
@@ -265,7 +267,7 @@ int launch_route(const grace_table *table, int32_t local_rank, grace_policy poli
     }
     int nbits = 0;
     while ((1 << nbits) < E) ++nbits;
-    const int mode = fold_mode(nchunks, E);
+    const int mode = fold_mode(table, nchunks, E);
     if (mode != 0) {
         const int32_t *super_tot = nullptr;
         if (mode == 2) {  // column sums per super-chunk of rows, into the (otherwise unused) scan buffer

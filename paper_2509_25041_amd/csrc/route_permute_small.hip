@@ -65,7 +65,8 @@ __global__ __launch_bounds__(SMALL_THREADS) void dispatch_small_kernel(
         valid = valid && (unsigned)e < (unsigned)E;
         if (j < n_w) asg[wave][j] = valid ? e : -1;
         const uint64_t same = wave_match((uint32_t)e, valid, ebits);
-        if (valid && is_last_of(same)) ecnt[wave][e] += (int32_t)__popcll(same);
+        if (valid && is_last_of(same)) wave_ctr_add(&ecnt[wave][e], (int32_t)__popcll(same));
+        wave_ctr_fence();
     }
     __syncthreads();
     // ---- 1. requests of each expert before each wavefront; totals -----------------------------
@@ -90,15 +91,16 @@ __global__ __launch_bounds__(SMALL_THREADS) void dispatch_small_kernel(
         const uint64_t same = wave_match((uint32_t)e, valid, ebits);
         int g = 0;
         if (valid) {
-            const uint64_t c = (uint64_t)(uint32_t)ecnt[wave][e] + (uint32_t)__popcll(same & lt) +
+            const uint64_t c = (uint64_t)(uint32_t)wave_ctr_load(&ecnt[wave][e]) + (uint32_t)__popcll(same & lt) +
                                (uint64_t)(rr_in ? rr_in[e] : 0u);
             g = pick_candidate(c, e, cand_ptr, cand_g, cand_cum);
             topk_inst[a0 + j] = g;
         }
         if (j < n_w) asg[wave][j] = valid ? g : -1;
-        if (valid && is_last_of(same)) ecnt[wave][e] += (int32_t)__popcll(same);
+        if (valid && is_last_of(same)) wave_ctr_add(&ecnt[wave][e], (int32_t)__popcll(same));
         const uint64_t same_g = wave_match((uint32_t)g, valid, ibits);
-        if (valid && is_last_of(same_g)) icnt[wave][g] += (int32_t)__popcll(same_g);
+        if (valid && is_last_of(same_g)) wave_ctr_add(&icnt[wave][g], (int32_t)__popcll(same_g));
+        wave_ctr_fence();
     }
     __syncthreads();
     // ---- 3. rows of each instance before each wavefront; offsets --------------------------------
@@ -147,13 +149,14 @@ __global__ __launch_bounds__(SMALL_THREADS) void dispatch_small_kernel(
         const int g = valid ? g_in : 0;
         const uint64_t same = wave_match((uint32_t)g, valid, ibits);
         if (valid) {
-            const int32_t pos = ioff[g] + icnt[wave][g] + (int32_t)__popcll(same & lt);
+            const int32_t pos = ioff[g] + wave_ctr_load(&icnt[wave][g]) + (int32_t)__popcll(same & lt);
             perm_pos[a0 + j] = pos;
             perm_src[pos] = (int32_t)(a0 + j);
         } else if (j < n_w) {
             perm_pos[a0 + j] = -1;  // expert id outside the table: no row
         }
-        if (valid && is_last_of(same)) icnt[wave][g] += (int32_t)__popcll(same);
+        if (valid && is_last_of(same)) wave_ctr_add(&icnt[wave][g], (int32_t)__popcll(same));
+        wave_ctr_fence();
     }
 }
 
@@ -191,7 +194,7 @@ extern "C" int grace_route_permute(const grace_table *table, int32_t local_rank,
         rc = launch_route(table, local_rank, policy, logits, T, E, k, renorm, rr_in, rr_out, topk_expert, topk_weight,
                           topk_inst, expert_count, ws, phist, st);
         if (rc != GRACE_OK) return rc;
-        const char *failed = stable_sort_launch(topk_inst, n, I, 1, phist, pbase, table->R, table->N, table->d_rank_ptr,
+        const char *failed = stable_sort_launch(table, topk_inst, n, I, 1, phist, pbase, table->R, table->N, table->d_rank_ptr,
                                                 table->d_node_first_inst, inst_off, rank_off, node_off, perm_pos, perm_src,
                                                 st, /*hist_ready=*/true);
         if (failed) return fail(GRACE_EHIP, "route_permute: launch of %s failed", failed);

@@ -125,9 +125,9 @@ __global__ __launch_bounds__(256) void expand_traffic_kernel(const int32_t *__re
     if (threadIdx.x < 4) traffic[threadIdx.x] = (int64_t)acc[threadIdx.x];
 }
 
-static int sort_by_key(const int32_t *keys, int64_t n, int k, int nkeys, int32_t *hist, int32_t *base, int32_t *off,
+static int sort_by_key(const grace_table *table, const int32_t *keys, int64_t n, int k, int nkeys, int32_t *hist, int32_t *base, int32_t *off,
                        int32_t *pos, int32_t *tok, hipStream_t st) {
-    const char *failed = stable_sort_launch(keys, n, nkeys, k, hist, base, 0, 0, nullptr, nullptr, off, nullptr, nullptr,
+    const char *failed = stable_sort_launch(table, keys, n, nkeys, k, hist, base, 0, 0, nullptr, nullptr, off, nullptr, nullptr,
                                             pos, tok, st);
     if (failed) return fail(GRACE_EHIP, "send_lists: launch of %s failed", failed);
     return GRACE_OK;
@@ -167,9 +167,9 @@ extern "C" int grace_send_lists(const grace_table *table, int32_t local_rank, co
                                                                          counters, R + 1);
         GRACE_LAUNCH_CHECK("dedup_keys_kernel");
     }
-    int rc = sort_by_key(rank_key, n, k, R, hist, base, rank_send_ptr, pos_r, rank_send_tok, st);
+    int rc = sort_by_key(table, rank_key, n, k, R, hist, base, rank_send_ptr, pos_r, rank_send_tok, st);
     if (rc != GRACE_OK) return rc;
-    rc = sort_by_key(node_key, n, k, N, hist, base, node_send_ptr, pos_n, node_send_tok, st);
+    rc = sort_by_key(table, node_key, n, k, N, hist, base, node_send_ptr, pos_n, node_send_tok, st);
     if (rc != GRACE_OK) return rc;
     if (n > 0 || traffic) {
         expand_traffic_kernel<<<(unsigned)std::max<int64_t>(1, ceil_div(n, 256)), 256, 0, st>>>(

@@ -105,13 +105,14 @@ __device__ __forceinline__ void rank_chunk(const int (&g_in)[CHUNK_ROUNDS], int6
         const bool valid = in && (unsigned)g < (unsigned)nkeys;
         const uint64_t same = wave_match((uint32_t)g, valid, nbits);
         if (valid) {
-            const int32_t pos = cnt[g] + (int32_t)__popcll(same & lt);
+            const int32_t pos = wave_ctr_load(&cnt[g]) + (int32_t)__popcll(same & lt);
             perm_pos[a] = pos;
             perm_src[pos] = (int32_t)(a / src_div);  // src_div = 1: the item itself; k: its token
         } else if (in) {
             perm_pos[a] = -1;  // key outside the table: no row
         }
-        if (valid && is_last_of(same)) cnt[g] += (int32_t)__popcll(same);
+        if (valid && is_last_of(same)) wave_ctr_add(&cnt[g], (int32_t)__popcll(same));
+        wave_ctr_fence();
     }
 }
 
@@ -223,7 +224,7 @@ static __global__ __launch_bounds__(POS_FOLD_THREADS) void key_pos_fold_kernel(
 // Host side: the launches of one stable counting sort.  hist / base: workspace of nchunks * nkeys
 // ints each.  rank_ptr .. node_off may be null (plain sort: only `off` is produced).
 // hist_ready: an earlier kernel on the stream already wrote the chunk histograms into `hist`.
-static inline const char *stable_sort_launch(const int32_t *keys, int64_t n, int nkeys, int src_div, int32_t *hist,
+static inline const char *stable_sort_launch(const grace_table *table, const int32_t *keys, int64_t n, int nkeys, int src_div, int32_t *hist,
                                              int32_t *base, int R, int N, const int32_t *rank_ptr,
                                              const int32_t *node_first_inst, int32_t *off, int32_t *rank_off,
                                              int32_t *node_off, int32_t *pos, int32_t *src, hipStream_t st,
@@ -235,7 +236,7 @@ static inline const char *stable_sort_launch(const int32_t *keys, int64_t n, int
         key_hist_kernel<<<nchunks, 64, 0, st>>>(keys, n, nkeys, hist);
         if (hipGetLastError() != hipSuccess) return "key_hist_kernel";
     }
-    const int mode = fold_mode(nchunks, nkeys);
+    const int mode = fold_mode(table, nchunks, nkeys);
     if (mode != 0) {
         const int32_t *super_tot = nullptr;
         if (mode == 2) {  // column sums per super-chunk of rows, into the (otherwise unused) scan buffer

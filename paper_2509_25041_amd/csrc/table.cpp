@@ -1,7 +1,6 @@
 // Placement / replica table: validation, dispatch order, per-rank candidate
 // tiers (Algorithm 4 evaluated once per (rank, expert) on the host), device copy.
 #include <algorithm>
-#include <atomic>
 #include <cstring>
 #include <new>
 #include <numeric>
@@ -225,15 +224,13 @@ extern "C" int grace_table_local_experts(const grace_table *t, int32_t rank, int
 }
 
 namespace grace {
-static std::atomic<int> g_fold_one_level{FOLD_ONE_LEVEL_DEFAULT}, g_fold_two_level{FOLD_TWO_LEVEL_DEFAULT};
-
-int fold_mode(int nchunks, int nkeys) {
+int fold_mode(const grace_table *table, int nchunks, int nkeys) {
     constexpr int64_t SUPER = 64;  // rows per super-chunk (FOLD_SUPER of the kernels)
     const int64_t kb = (nkeys + 63) / 64;
     if (nchunks < 1) return 0;
-    if (nchunks * kb <= g_fold_one_level.load(std::memory_order_relaxed)) return 1;
+    if (nchunks * kb <= table->fold_one_level) return 1;
     const int64_t nsuper = (nchunks + SUPER - 1) / SUPER;
-    return (nsuper + SUPER) * kb <= g_fold_two_level.load(std::memory_order_relaxed) ? 2 : 0;
+    return (nsuper + SUPER) * kb <= table->fold_two_level ? 2 : 0;
 }
 
 size_t fused_perm_ws_offset(int32_t T, int32_t E) {
@@ -241,9 +238,10 @@ size_t fused_perm_ws_offset(int32_t T, int32_t E) {
 }
 }  // namespace grace
 
-extern "C" int grace_set_fold_limits(int32_t one_level_max, int32_t two_level_max) {
-    grace::g_fold_one_level.store(one_level_max < 0 ? grace::FOLD_ONE_LEVEL_DEFAULT : one_level_max, std::memory_order_relaxed);
-    grace::g_fold_two_level.store(two_level_max < 0 ? grace::FOLD_TWO_LEVEL_DEFAULT : two_level_max, std::memory_order_relaxed);
+extern "C" int grace_table_set_fold_limits(grace_table *table, int32_t one_level_max, int32_t two_level_max) {
+    if (!table) return fail(GRACE_EINVAL, "table_set_fold_limits: table is null");
+    table->fold_one_level = one_level_max < 0 ? grace::FOLD_ONE_LEVEL_DEFAULT : one_level_max;
+    table->fold_two_level = two_level_max < 0 ? grace::FOLD_TWO_LEVEL_DEFAULT : two_level_max;
     return GRACE_OK;
 }
 

@@ -48,6 +48,22 @@ __device__ __forceinline__ bool is_last_of(uint64_t same) {
     const uint64_t above = (l == 63) ? 0ull : (same >> (l + 1));
     return above == 0ull;
 }
+// LDS counters that one wavefront updates in one round of a loop and reads in the next (the highest
+// lane of a match set adds the set's size; other lanes read the counter a round later).  LDS
+// operations of one wavefront execute in program order; relaxed atomic accesses (plain ds_read /
+// ds_write on this target) with a wavefront-scope fence between the rounds make that hand-over
+// defined for the compiler as well.
+template <typename T>
+__device__ __forceinline__ T wave_ctr_load(const T *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+}
+template <typename T>
+__device__ __forceinline__ void wave_ctr_add(T *p, T v) {
+    __hip_atomic_store(p, (T)(__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) + v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_WAVEFRONT);
+}
+__device__ __forceinline__ void wave_ctr_fence() { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); }
+
 __device__ __forceinline__ int bits_for(int nkeys) {
     int b = 0;
     while ((1 << b) < nkeys) ++b;

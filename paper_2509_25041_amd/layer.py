@@ -7,9 +7,9 @@ from typing import List, Optional, Tuple
 
 import torch
 
-from .binding import GraceTable, _check, _dtype_code, grace_workspace_bytes, load_library
+from .binding import SHARE_STATE_INTS, GraceTable, _check, _dtype_code, grace_workspace_bytes, load_library
 
-STAGES = ("route", "permute", "route_permute", "ffn_up", "ffn_down", "shared_ffn", "combine")
+STAGES = ("route", "permute", "route_permute", "ffn_up", "ffn_down", "shared_up", "shared_down", "combine")
 
 
 class GraceMoELayer:
@@ -17,10 +17,14 @@ class GraceMoELayer:
 
     Weights are stacked in the slot order of `local_rank`
     (GraceTable.local_experts): w_gate, w_up [S,f,d]; w_down [S,d,f].
-    Rows of other ranks stay zero in `y` (their results would arrive over the
-    reverse all-to-all in a multi-GPU deployment).
+    Rows of other ranks are zero in `y` on every step (their results would arrive
+    over the reverse all-to-all in a multi-GPU deployment): the rank's row range
+    moves with the routing, so each step clears what an earlier step wrote outside
+    the current range (grace_expert_ffn_up_share / _down_share do it inside the
+    two projections' launches: no extra launch, no memset, the step stays capturable
+    in a HIP graph).
 
-    All buffers are allocated once; a step is four or five C calls whose argument lists
+    All buffers are allocated once; a step is four to six C calls whose argument lists
     are marshalled once per (logits, x, rr_in, rr_out, stream) and reused, so the
     host cost of a step is a few microseconds per call.
     """
@@ -52,6 +56,7 @@ class GraceMoELayer:
                          torch.empty(table.R + 1, **i32), torch.empty(table.N + 1, **i32))
         self.xp = torch.empty((n, d), dtype=dtype, device=device)
         self.y = torch.zeros((n, d), dtype=dtype, device=device)
+        self.y_state = torch.zeros(SHARE_STATE_INTS, **i32)   # row range of y written by the previous step (grace_expert_ffn_up_share / _down_share)
         self.y_shared = torch.empty((T, d), dtype=dtype, device=device) if self.n_shared else None
         self.out = torch.empty((T, d), dtype=dtype, device=device)
         self.dt = _dtype_code(self.xp)
@@ -92,15 +97,16 @@ class GraceMoELayer:
                                                 p(self.xp), ws, st)),
             ]
         calls += [
-            ("ffn_up", lib.grace_expert_ffn_up, (h, lr, p(self.xp), p(ioff), T, k, d, f, dt, p(wg) if S else None,
-                                                 p(wu) if S else None, ws, st)),
-            ("ffn_down", lib.grace_expert_ffn_down, (h, lr, p(ioff), T, k, d, f, dt, p(wd) if S else None, p(self.y),
-                                                     ws, st)),
+            ("ffn_up", lib.grace_expert_ffn_up_share, (h, lr, p(self.xp), p(ioff), T, k, d, f, dt, p(wg) if S else None,
+                                                       p(wu) if S else None, p(self.y_state), ws, st)),
+            ("ffn_down", lib.grace_expert_ffn_down_share, (h, lr, p(ioff), T, k, d, f, dt, p(wd) if S else None,
+                                                           p(self.y), p(self.y_state), ws, st)),
         ]
         if self.shared is not None:
             sg, su, sd = self.shared
-            calls.append(("shared_ffn", lib.grace_shared_ffn, (p(x), T, d, f, self.n_shared, dt, p(sg), p(su), p(sd),
-                                                               p(self.y_shared), ws, st)))
+            calls.append(("shared_up", lib.grace_shared_ffn_up, (p(x), T, d, f, self.n_shared, dt, p(sg), p(su), ws, st)))
+            calls.append(("shared_down", lib.grace_shared_ffn_down, (T, d, f, self.n_shared, dt, p(sd), p(self.y_shared),
+                                                                     ws, st)))
         calls.append(("combine", lib.grace_combine, (p(self.y), p(pos), p(tw), T, k, d, dt, p(self.y_shared),
                                                      p(self.out), st)))
         return calls

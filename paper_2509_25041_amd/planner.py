@@ -30,15 +30,16 @@ def n_replica(w_max: float, w_mean: float, n_gpu: int) -> int:
 
 def hot_experts(loads: Sequence[float], experts: Sequence[int], w_max: float, n_rep: int) -> List[int]:
     """Section 4.2: inside the heaviest group, experts ranked by load (descending, ties to the lower
-    id); the leading ones up to and including the one whose cumulative load reaches
-    W_max * n_rep / (1 + n_rep)."""
+    id); the leading ones up to and including the first whose cumulative load exceeds
+    W_max * n_rep / (1 + n_rep) (strictly: a cumulative load equal to the threshold does not end
+    the hot set)."""
     order = sorted(experts, key=lambda e: (-loads[e], e))
     thr = w_max * n_rep / (1.0 + n_rep)
     out, cum = [], 0.0
     for e in order:
         out.append(e)
         cum += loads[e]
-        if cum >= thr:
+        if cum > thr:
             break
     return out
 

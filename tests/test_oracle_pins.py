@@ -139,6 +139,21 @@ def test_send_lists_worked_examples():
     assert sl.traffic.tolist() == c["traffic"]
 
 
+@pytest.mark.parametrize("case", ["case_from_larger_node", "case_from_smaller_node"])
+def test_send_lists_nodes_of_unequal_size(case):
+    """Stage-1 peer in a node of another size: index inside the own node, modulo that node's size."""
+    g = gold("send_lists_unequal_nodes.json")
+    pl = table_from(g)
+    order = oracle.instance_order(pl)
+    assert order.g_rank.tolist() == [0, 1, 2, 3, 4] and order.g_expert.tolist() == [0, 1, 0, 1, 2]
+    c = g[case]
+    sl = oracle.send_lists(np.array(c["topk_inst"], np.int32), pl, c["local_rank"])
+    assert sl.rank_send_ptr.tolist() == c["rank_send_ptr"] and sl.rank_send_tok.tolist() == c["rank_send_tok"]
+    assert sl.node_send_ptr.tolist() == c["node_send_ptr"] and sl.node_send_tok.tolist() == c["node_send_tok"]
+    assert sl.expand.tolist() == c["expand"]
+    assert sl.traffic.tolist() == c["traffic"]
+
+
 @pytest.mark.parametrize("name,local_rank", [("olmoe", 0), ("dsv2lite", 13), ("qwen", 5)])
 def test_send_lists_against_library_unique(name, local_rank):
     cfg = CONFIGS[name]

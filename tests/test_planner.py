@@ -17,8 +17,19 @@ def test_closed_forms_by_hand():
     # heaviest group loads 50, 30, 15, 5 (W_max = 100), n_replica = 2: threshold 66.7 -> the first two
     loads = {0: 50.0, 1: 30.0, 2: 15.0, 3: 5.0}
     assert planner.hot_experts(loads, [3, 1, 0, 2], 100.0, 2) == [0, 1]
-    assert planner.hot_experts(loads, [0, 1, 2, 3], 100.0, 1) == [0]           # threshold 50 reached at once
+    # threshold 50 is met exactly by the first expert: "exceeds" is strict, so the second one is hot as well
+    assert planner.hot_experts(loads, [0, 1, 2, 3], 100.0, 1) == [0, 1]
+    assert planner.hot_experts({0: 51.0, 1: 29.0, 2: 15.0, 3: 5.0}, [0, 1, 2, 3], 100.0, 1) == [0]   # 51 > 50 at once
     assert planner.hot_experts({0: 10.0, 1: 10.0}, [1, 0], 20.0, 3) == [0, 1]  # ties: lower id first
+
+
+def test_equation_3_agrees_with_the_input_generator():
+    """The workload generator applies Equation 3 when it lays out config 4's table (input data for both
+    the HIP path and the oracle, so it cannot import the planner); the two must be the same function."""
+    from workloads.generator import eq3_n_replica
+    for n_gpu in (2, 4, 8, 32):
+        for rho in (0.3, 0.99, 1.0, 1.5, 2.0, 2.7, 7.9, 8.0, 31.0, 40.0):
+            assert planner.n_replica(rho * 3.0, 3.0, n_gpu) == eq3_n_replica(rho * 3.0, 3.0, n_gpu)
 
 
 def test_plan_by_hand():
