@@ -62,6 +62,7 @@ typedef enum {
 #define GRACE_MAX_RANKS 1024    /* R                        */
 #define GRACE_MAX_INSTANCES 4096 /* I                       */
 #define GRACE_MAX_POLL_WEIGHT 65535u
+#define GRACE_STATIC_SCRATCH_BYTES (4u << 20) /* scratch of grace_route_permute_static, per GPU */
 #define GRACE_SHARE_STATE_INTS 8 /* size of the state of grace_expert_ffn_up_share / _down_share */
 
 typedef struct grace_table grace_table; /* opaque; owns host and device copies */
@@ -191,6 +192,28 @@ int grace_route_permute(const grace_table *table, int32_t local_rank, grace_poli
                         int32_t *topk_expert, float *topk_weight, int32_t *topk_inst, int32_t *expert_count,
                         const void *x, int32_t d, grace_dtype dt, int32_t *perm_pos, int32_t *perm_src,
                         int32_t *inst_off, int32_t *rank_off, int32_t *node_off, void *xp, void *ws, void *stream);
+
+/* ---- grace_route_permute_static: grace_route_permute without a workspace -------
+ * For callers that cannot allocate device memory or hand one in: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus ws), outputs (bit
+ * for bit) and errors as grace_route_permute; the index kernels' scratch is a static device array of
+ * GRACE_STATIC_SCRATCH_BYTES that every GPU the library runs on holds from its first use until
+ * the process ends.  The call allocates and frees nothing (no hipMalloc, no hipFree, no allocating
+ * library routine); its first use on a device looks the array's address up once.
+ * Limit: sizes whose histograms do not fit the array are rejected with GRACE_ESHAPE and a text
+ * that says so (needed bytes = 16 * ceil(T / 16) * E + 8 * ceil(T * k / 512) * I, each term rounded
+ * up to 256: e.g. T = 32768, E = 64, k = 6, I = 88 needs 2.3 MB; T = 100 000 with E = 128 does not
+ * fit) - use grace_route_permute with a workspace then.
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on the same GPU (on
+ * different streams or from different threads) race on it and must be serialised by the caller;
+ * calls on one stream are ordered and safe.  Nothing in the array has to be zero on entry and a
+ * call leaves its histograms behind.
+ */
+int grace_route_permute_static(const grace_table *table, int32_t local_rank, grace_policy policy, const float *logits,
+                               int32_t T, int32_t E, int32_t k, int32_t renorm, const uint32_t *rr_in, uint32_t *rr_out,
+                               int32_t *topk_expert, float *topk_weight, int32_t *topk_inst, int32_t *expert_count,
+                               const void *x, int32_t d, grace_dtype dt, int32_t *perm_pos, int32_t *perm_src,
+                               int32_t *inst_off, int32_t *rank_off, int32_t *node_off, void *xp, void *stream);
 
 /* ---- grace_send_lists: de-duplicated hierarchical send lists ------------------
  * Section 5: a token with several experts on one destination crosses the link

@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     grace_permute,
     grace_route,
     grace_route_permute,
+    grace_route_permute_static,
     grace_send_lists,
     grace_shared_ffn,
     grace_table_validate,

@@ -19,7 +19,7 @@ _STATUS = {0: "GRACE_OK", -1: "GRACE_EINVAL", -2: "GRACE_ESHAPE", -3: "GRACE_ETA
 EXPORTS = ("grace_table_validate", "grace_table_create", "grace_table_destroy", "grace_table_info",
            "grace_table_instances", "grace_table_local_experts", "grace_table_set_fold_limits", "grace_workspace_bytes",
            "grace_route",
-           "grace_permute", "grace_route_permute", "grace_send_lists", "grace_expert_ffn", "grace_expert_ffn_up",
+           "grace_permute", "grace_route_permute", "grace_route_permute_static", "grace_send_lists", "grace_expert_ffn", "grace_expert_ffn_up",
            "grace_expert_ffn_down", "grace_expert_ffn_up_share", "grace_expert_ffn_down_share",
            "grace_shared_ffn", "grace_shared_ffn_up", "grace_shared_ffn_down", "grace_combine", "grace_mfma_sustained",
            "grace_last_error")
@@ -63,6 +63,8 @@ def load_library() -> C.CDLL:
     lib.grace_permute.argtypes = [vp, vp, i32, i32, vp, i32, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.grace_route_permute.argtypes = [vp, i32, C.c_int, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp,
                                         vp, i32, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.grace_route_permute_static.argtypes = [vp, i32, C.c_int, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp,
+                                               vp, i32, C.c_int, vp, vp, vp, vp, vp, vp, vp]
     lib.grace_send_lists.argtypes = [vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.grace_expert_ffn.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp, vp]
     lib.grace_expert_ffn_up.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp]
@@ -253,6 +255,32 @@ def grace_route_permute(table: GraceTable, local_rank: int, logits: torch.Tensor
                                               _dp(src), _dp(ioff), _dp(roff), _dp(noff),
                                               _dp(xp) if x is not None else None, _dp(ws), _stream()))
     return (te, tw, ti, cnt), (pos, src, ioff, roff, noff, xp)
+
+
+def grace_route_permute_static(table: GraceTable, local_rank: int, logits: torch.Tensor, k: int, x: Optional[torch.Tensor],
+                               renorm: int = 1, rr_in: Optional[torch.Tensor] = None, rr_out: Optional[torch.Tensor] = None,
+                               policy: int = GRACE_POLICY_TAR, out=None):
+    """grace_route_permute on the library's static scratch instead of a workspace (see grace_moe.h).
+    `out` = ((topk_expert, topk_weight, topk_inst, expert_count), (perm_pos, perm_src, inst_off, rank_off,
+    node_off, xp)) reuses the caller's output tensors; the C call itself allocates nothing."""
+    T, E = logits.shape
+    dev = logits.device
+    if logits.dtype != torch.float32:
+        raise ValueError("logits must be float32")
+    d, dt = (0, GRACE_BF16) if x is None else (x.shape[1], _dtype_code(x))
+    if out is None:
+        i32 = dict(dtype=torch.int32, device=dev)
+        out = ((torch.empty((T, k), **i32), torch.empty((T, k), dtype=torch.float32, device=dev), torch.empty((T, k), **i32),
+                torch.empty((E,), **i32)),
+               (torch.empty(T * k, **i32), torch.empty(T * k, **i32), torch.empty(table.I + 1, **i32),
+                torch.empty(table.R + 1, **i32), torch.empty(table.N + 1, **i32),
+                None if x is None else torch.empty((T * k, d), dtype=x.dtype, device=dev)))
+    (te, tw, ti, cnt), (pos, src, ioff, roff, noff, xp) = out
+    _check(load_library().grace_route_permute_static(table.handle, local_rank, policy, _dp(logits), T, E, k, renorm, _dp(rr_in),
+                                                     _dp(rr_out), _dp(te), _dp(tw), _dp(ti), _dp(cnt), _dp(x), d, dt, _dp(pos),
+                                                     _dp(src), _dp(ioff), _dp(roff), _dp(noff),
+                                                     _dp(xp) if x is not None else None, _stream()))
+    return out
 
 
 def grace_send_lists(table: GraceTable, local_rank: int, topk_inst: torch.Tensor, ws: Optional[torch.Tensor] = None):

@@ -74,6 +74,8 @@ int launch_route(const grace_table *table, int32_t local_rank, grace_policy poli
 // Byte offset, inside the workspace, of the permutation's histograms when routing and permutation
 // share one call (the routing histograms of the same call lie below it).
 size_t fused_perm_ws_offset(int32_t T, int32_t E);
+// Workspace bytes of routing + permutation as one call (both sets of histograms and their prefix sums).
+size_t route_permute_ws_bytes(int32_t T, int32_t E, int32_t k, int32_t I);
 int launch_scatter_rows(const void *x, int T, int k, int d, grace_dtype dt, const int32_t *perm_pos, void *xp,
                         hipStream_t st);
 

@@ -15,6 +15,8 @@
 //   4. positions           stable rank of every assignment in (node, rank, slot) order (Section 5)
 // and by the row scatter: three launches.
 // Outputs are identical either way (all integer work is exact and order-independent).
+#include <mutex>
+
 #include "common.h"
 #include "route_device.h"
 #include "stable_sort.h"
@@ -164,18 +166,13 @@ __global__ __launch_bounds__(SMALL_THREADS) void dispatch_small_kernel(
 
 using namespace grace;
 
-extern "C" int grace_route_permute(const grace_table *table, int32_t local_rank, grace_policy policy, const float *logits,
-                                   int32_t T, int32_t E, int32_t k, int32_t renorm, const uint32_t *rr_in,
-                                   uint32_t *rr_out, int32_t *topk_expert, float *topk_weight, int32_t *topk_inst,
-                                   int32_t *expert_count, const void *x, int32_t d, grace_dtype dt, int32_t *perm_pos,
-                                   int32_t *perm_src, int32_t *inst_off, int32_t *rank_off, int32_t *node_off, void *xp,
-                                   void *ws, void *stream) {
-    int rc = check_route_args(table, local_rank, policy, logits, T, E, k, rr_in, rr_out, topk_expert, topk_weight, topk_inst,
-                              expert_count, ws);
-    if (rc != GRACE_OK) return rc;
-    rc = check_permute_args(table, topk_inst, T, k, x, d, dt, perm_pos, perm_src, inst_off, rank_off, node_off, xp, ws);
-    if (rc != GRACE_OK) return rc;
+static int route_permute_impl(const grace_table *table, int32_t local_rank, grace_policy policy, const float *logits,
+                             int32_t T, int32_t E, int32_t k, int32_t renorm, const uint32_t *rr_in, uint32_t *rr_out,
+                             int32_t *topk_expert, float *topk_weight, int32_t *topk_inst, int32_t *expert_count,
+                             const void *x, int32_t d, grace_dtype dt, int32_t *perm_pos, int32_t *perm_src,
+                             int32_t *inst_off, int32_t *rank_off, int32_t *node_off, void *xp, void *ws, void *stream) {
     hipStream_t st = (hipStream_t)stream;
+    int rc;
     // the shared-histogram path counts with 32-bit indices; sizes beyond that take the two calls
     const bool hist_fits = ceil_div((int64_t)T * k, PERM_CHUNK) * table->I <= (int64_t)1 << 30;
     if (T == 0 || !hist_fits) {
@@ -211,4 +208,76 @@ extern "C" int grace_route_permute(const grace_table *table, int32_t local_rank,
     GRACE_LAUNCH_CHECK("dispatch_small_kernel");
     if (x) return launch_scatter_rows(x, T, k, d, dt, perm_pos, xp, st);
     return GRACE_OK;
+}
+
+extern "C" int grace_route_permute(const grace_table *table, int32_t local_rank, grace_policy policy, const float *logits,
+                                   int32_t T, int32_t E, int32_t k, int32_t renorm, const uint32_t *rr_in,
+                                   uint32_t *rr_out, int32_t *topk_expert, float *topk_weight, int32_t *topk_inst,
+                                   int32_t *expert_count, const void *x, int32_t d, grace_dtype dt, int32_t *perm_pos,
+                                   int32_t *perm_src, int32_t *inst_off, int32_t *rank_off, int32_t *node_off, void *xp,
+                                   void *ws, void *stream) {
+    int rc = check_route_args(table, local_rank, policy, logits, T, E, k, rr_in, rr_out, topk_expert, topk_weight, topk_inst,
+                              expert_count, ws);
+    if (rc != GRACE_OK) return rc;
+    rc = check_permute_args(table, topk_inst, T, k, x, d, dt, perm_pos, perm_src, inst_off, rank_off, node_off, xp, ws);
+    if (rc != GRACE_OK) return rc;
+    return route_permute_impl(table, local_rank, policy, logits, T, E, k, renorm, rr_in, rr_out, topk_expert, topk_weight,
+                              topk_inst, expert_count, x, d, dt, perm_pos, perm_src, inst_off, rank_off, node_off, xp, ws,
+                              stream);
+}
+
+// ---- the same call for callers that cannot allocate ------------------------------------------------
+// The index kernels' scratch (chunk histograms and their prefix sums) lives in a file-scope device
+// array instead of a caller-provided workspace.  Every GPU the library runs on holds its own copy of
+// the array at its own address until the process ends; the address is looked up once per device, with
+// that device current, and from then on only that pointer is used on the host side (kernel arguments):
+// the array's name itself is no device address in host code.
+static __device__ __align__(256) unsigned char scratch[GRACE_STATIC_SCRATCH_BYTES];
+
+static int static_scratch(void **out) {
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static void *ptr[MAX_DEVICES] = {nullptr};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(GRACE_EHIP, "route_permute_static: hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(GRACE_EHIP, "route_permute_static: device %d not supported", dev);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(GRACE_EHIP, "route_permute_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return GRACE_OK;
+}
+
+extern "C" int grace_route_permute_static(const grace_table *table, int32_t local_rank, grace_policy policy,
+                                          const float *logits, int32_t T, int32_t E, int32_t k, int32_t renorm,
+                                          const uint32_t *rr_in, uint32_t *rr_out, int32_t *topk_expert, float *topk_weight,
+                                          int32_t *topk_inst, int32_t *expert_count, const void *x, int32_t d,
+                                          grace_dtype dt, int32_t *perm_pos, int32_t *perm_src, int32_t *inst_off,
+                                          int32_t *rank_off, int32_t *node_off, void *xp, void *stream) {
+    if (!table) return fail(GRACE_EINVAL, "route_permute_static: table is null");
+    void *ws = nullptr;
+    int rc = static_scratch(&ws);
+    if (rc != GRACE_OK) return rc;
+    rc = check_route_args(table, local_rank, policy, logits, T, E, k, rr_in, rr_out, topk_expert, topk_weight, topk_inst,
+                          expert_count, ws);
+    if (rc != GRACE_OK) return rc;
+    rc = check_permute_args(table, topk_inst, T, k, x, d, dt, perm_pos, perm_src, inst_off, rank_off, node_off, xp, ws);
+    if (rc != GRACE_OK) return rc;
+    const size_t need = route_permute_ws_bytes(T, E, k, table->I);
+    if (need > (size_t)GRACE_STATIC_SCRATCH_BYTES)
+        return fail(GRACE_ESHAPE,
+                    "route_permute_static: T=%d, E=%d, k=%d, I=%d need %zu bytes of scratch, the static buffer holds %zu; "
+                    "use grace_route_permute with a workspace",
+                    T, E, k, table->I, need, (size_t)GRACE_STATIC_SCRATCH_BYTES);
+    // nothing in the scratch has to start at zero: every kernel of the call writes the histogram
+    // rows and counters it later reads (the top-k kernel clears the permutation's counters)
+    return route_permute_impl(table, local_rank, policy, logits, T, E, k, renorm, rr_in, rr_out, topk_expert, topk_weight,
+                              topk_inst, expert_count, x, d, dt, perm_pos, perm_src, inst_off, rank_off, node_off, xp, ws,
+                              stream);
 }

@@ -236,6 +236,11 @@ int fold_mode(const grace_table *table, int nchunks, int nkeys) {
 size_t fused_perm_ws_offset(int32_t T, int32_t E) {
     return 2 * align_up((size_t)ceil_div(T, ROUTE_CHUNK_SMALL) * (size_t)E * 4, 256);
 }
+
+size_t route_permute_ws_bytes(int32_t T, int32_t E, int32_t k, int32_t I) {
+    const size_t chunks_p = (size_t)ceil_div((int64_t)T * k, PERM_CHUNK);
+    return fused_perm_ws_offset(T, E) + 2 * align_up(chunks_p * (size_t)I * 4, 256);
+}
 }  // namespace grace
 
 extern "C" int grace_table_set_fold_limits(grace_table *table, int32_t one_level_max, int32_t two_level_max) {
@@ -253,7 +258,7 @@ extern "C" size_t grace_workspace_bytes(int32_t T, int32_t E, int32_t k, int32_t
     const size_t n = (size_t)T * (size_t)k;
     const size_t chunks_p = (size_t)grace::ceil_div((int64_t)n, grace::PERM_CHUNK);
     // routing and permutation histograms side by side (grace_route_permute uses both at once)
-    size_t need = grace::fused_perm_ws_offset(T, E) + 2 * grace::align_up(chunks_p * (size_t)I * 4, 256);
+    size_t need = grace::route_permute_ws_bytes(T, E, k, I);
     need = std::max(need, grace::align_up(n * (size_t)f * el, 256));
     need = std::max(need, grace::align_up((size_t)T * (size_t)n_shared * (size_t)f * el, 256));
     // send lists: five int32 arrays over the assignments + chunk histograms over up to GRACE_MAX_RANKS keys + counters

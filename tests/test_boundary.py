@@ -76,6 +76,8 @@ def test_null_and_range_checks_without_device():
     assert lib.grace_combine(None, None, None, 0, 1, 8, 1, None, None, None) == 0                # nothing to do
     assert lib.grace_mfma_sustained(1, 1, None, None) == -1
     assert lib.grace_table_set_fold_limits(None, -1, -1) == -1
+    assert lib.grace_route_permute_static(None, 0, 0, None, 1, 1, 1, 1, None, None, None, None, None, None, None, 8, 1, None,
+                                          None, None, None, None, None, None) == -1
     assert lib.grace_expert_ffn_up_share(None, 0, None, None, 1, 1, 8, 8, 1, None, None, None, None, None) == -1
     assert lib.grace_expert_ffn_down_share(None, 0, None, 1, 1, 8, 8, 1, None, None, None, None, None) == -1
     assert lib.grace_send_lists(None, 0, None, 1, 1, None, None, None, None, None, None, None, None) == -1
