@@ -127,14 +127,27 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     const int rounds_f = (j_each + (j_rem ? 1 : 0) + nblk - 1) / nblk;
     const bool flat = rounds_f < rounds_m;                            // uniform
     const bool m_fastest = n_tiles_n > total_mt;
-    const int njobs = flat ? j_each + (xcd < j_rem ? 1 : 0) : (mt_each + (xcd < mt_rem ? 1 : 0)) * n_tiles_n;
-    auto job_mt = [&](int job) {
-        const int q = j_first + job;
-        return flat ? (m_fastest ? q % total_mt : q / n_tiles_n) : mt_first + job / n_tiles_n;
-    };
-    auto job_n0 = [&](int job) {
-        const int q = j_first + job;
-        return (flat ? (m_fastest ? q / total_mt : q % n_tiles_n) : job % n_tiles_n) * BN;
+    const int njobs = flat ? j_each + (xcd < j_rem ? 1 : 0) : (mt_each + (xcd < mt_rem ? 1 : 0)) * n_tiles_n;  // >= 0
+    // By m-tile, the XCD's tiles are walked in panels of PANEL_M m-tiles x PANEL_N n-tiles (m running
+    // fastest inside a panel, then the panels of one group of m-tiles side by side): the workgroups of
+    // an XCD, which take consecutive jobs, then share PANEL_M activation tiles and PANEL_N weight tiles
+    // at any time, and the XCD's L2 is filled with PANEL_M + PANEL_N tiles per round of tiles instead
+    // of about one activation tile plus every weight tile of the row.
+    const int my_mt = mt_each + (xcd < mt_rem ? 1 : 0);
+    const int PANEL_N = min(n_tiles_n, 4), PANEL_M = max(1, nblk / PANEL_N);
+    auto job_tile = [&](int job, int &mt, int &n0) {
+        if (flat) {
+            const int q = j_first + job;
+            mt = m_fastest ? q % total_mt : q / n_tiles_n;
+            n0 = (m_fastest ? q / total_mt : q % n_tiles_n) * BN;
+        } else {
+            const int per_group = PANEL_M * n_tiles_n;
+            const int mg = job / per_group, r = job - mg * per_group;
+            const int gm = min(PANEL_M, my_mt - mg * PANEL_M);   // m-tiles of this group (the last may be short)
+            const int ng = r / (gm * PANEL_N), r2 = r - ng * gm * PANEL_N;
+            mt = mt_first + mg * PANEL_M + r2 % gm;
+            n0 = (ng * PANEL_N + r2 / gm) * BN;
+        }
     };
     // rank-share upkeep of the expert down projection's output (no-op unless the launcher asks for it)
     if (WHO == EXPERTS) {
@@ -410,8 +423,9 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     // ---- tile loop ----------------------------------------------------------------------------------
     // Per tile of nk steps: steps 0 .. nk-3 load this tile's steps 2 .. nk-1; steps nk-2 and nk-1
     // load steps 0 and 1 of the next tile, if there is one.
-    Tile cur = lookup(job_mt(job));
-    int cur_n0 = job_n0(job);
+    int cur_mt, cur_n0;
+    job_tile(job, cur_mt, cur_n0);
+    Tile cur = lookup(cur_mt);
     set_a_sources(cur);
     set_b_sources(cur, cur_n0);
     issue_a();
@@ -426,8 +440,9 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
         Tile nxt = cur;
         int nxt_n0 = cur_n0;
         if (has_next) {
-            nxt = lookup(job_mt(next_job));
-            nxt_n0 = job_n0(next_job);
+            int nxt_mt;
+            job_tile(next_job, nxt_mt, nxt_n0);
+            nxt = lookup(nxt_mt);
         }
         // 32-row sub-tiles of this wavefront that hold at least one valid row (scalar)
         const int n_valid = max(0, min(4, (cur.m_end - (cur.m0 + wm * 128) + 31) / 32));
