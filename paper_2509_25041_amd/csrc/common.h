@@ -35,10 +35,14 @@ const char *last_error();
 constexpr int WAVE = 64;
 
 // Assignments are ranked in chunks; one wavefront owns one chunk.
-// route: chunk = 16 tokens (small batches: more workgroups) or 32 tokens (large batches: fewer
-// histogram rows to scan); the workspace is sized for the smaller one
-constexpr int ROUTE_CHUNK_SMALL = 16, ROUTE_CHUNK_LARGE = 32, ROUTE_SMALL_CHUNK_MAX_T = 8192;
-inline int route_chunk_tokens(int T) { return T <= ROUTE_SMALL_CHUNK_MAX_T ? ROUTE_CHUNK_SMALL : ROUTE_CHUNK_LARGE; }
+// route: the top-k kernel writes one histogram row per chunk of 16 tokens (small batches: more
+// workgroups), 32 or 64 tokens (large batches: fewer histogram rows to sum); the workspace is sized
+// for the smallest one
+constexpr int ROUTE_CHUNK_SMALL = 16, ROUTE_CHUNK_LARGE = 32, ROUTE_CHUNK_HUGE = 64;
+constexpr int ROUTE_SMALL_CHUNK_MAX_T = 8192, ROUTE_LARGE_CHUNK_MAX_T = 16384;
+inline int route_chunk_tokens(int T) {
+    return T <= ROUTE_SMALL_CHUNK_MAX_T ? ROUTE_CHUNK_SMALL : T <= ROUTE_LARGE_CHUNK_MAX_T ? ROUTE_CHUNK_LARGE : ROUTE_CHUNK_HUGE;
+}
 constexpr int PERM_CHUNK = 512;              // permute: chunk = 512 assignments
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

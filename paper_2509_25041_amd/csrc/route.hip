@@ -10,10 +10,11 @@
 //   2. route_scan    exclusive scan of the chunk histograms per expert -> the
 //                    number of earlier requests of each expert before each chunk
 //                    (the weighted round-robin counter of Section 4.3);
-//   3. pick_kernel   one wavefront per chunk walks its assignments in order, ranks
-//                    equal experts with ballot-based matching, and maps request
-//                    number c to the candidate of the tier Algorithm 4 selects
-//                    whose cumulative polling-weight interval holds c mod W.
+//   3. pick_kernel   one workgroup per 64 tokens walks their assignments in order (every
+//                    wavefront 64 of them at a time), ranks equal experts with ballot-based
+//                    matching, and maps request number c to the candidate of the tier
+//                    Algorithm 4 selects whose cumulative polling-weight interval holds
+//                    c mod W.
 #include "common.h"
 #include "route_device.h"
 #include "wave_utils.h"
@@ -91,46 +92,48 @@ __global__ __launch_bounds__(SCAN_THREADS) void route_scan_kernel(const int32_t 
     }
 }
 
-// FOLD = false: chunk_counts is the scanned histogram (requests of each expert before each chunk).
-// FOLD = true: chunk_counts is the raw per-chunk histogram; the block sums the rows before its own,
+// One workgroup picks the replicas of PICK_TOKENS consecutive tokens = rows_per_block rows of the
+// top-k kernel's chunk histograms.
+// FOLD = false: chunk_counts is the scanned histogram (requests of each expert before each row).
+// FOLD = true: chunk_counts is the raw per-row histogram; the block sums the rows before its own,
 // and the last block also writes expert_count and rr_out.
+// The assignments are walked in rounds of PICK_THREADS, every wavefront taking 64 consecutive ones:
+// it matches equal experts with ballots and leaves the size of every match set in its row of wcnt;
+// an exclusive scan over the eight rows, continued from cnt (requests before this round), gives each
+// wavefront the number of earlier requests of every expert, and request number c of expert e maps to
+// the candidate of the tier Algorithm 4 selects whose cumulative polling-weight interval holds c mod W.
 // With inst_hist (zeroed beforehand) every pick is also counted per chunk of PERM_CHUNK assignments
 // and instance: the histogram the dispatch permutation starts from (integer atomics: exact in any order).
 constexpr int PICK_LDS_CANDS = 1024;  // candidate entries of one view that are staged in LDS (else read from global memory)
-constexpr int PICK_BATCH = 4;         // rounds of 64 assignments whose experts are fetched together
-constexpr int PICK_THREADS = 512;  // wavefront 0 ranks; all eight sum histogram rows when FOLD
+constexpr int PICK_THREADS = 512, PICK_WAVES = PICK_THREADS / 64;
+constexpr int PICK_TOKENS = 64;       // tokens per workgroup
 
 template <bool FOLD>
 __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__restrict__ topk_expert, int64_t n_assign,
                                                             int E, int k, const int32_t *__restrict__ chunk_counts,
-                                                            int nchunks, const uint32_t *__restrict__ rr_in,
+                                                            int nrows, int rows_per_block,
+                                                            const uint32_t *__restrict__ rr_in,
                                                             uint32_t *__restrict__ rr_out,
                                                             int32_t *__restrict__ expert_count,
                                                             const int32_t *__restrict__ cand_ptr,
                                                             const int32_t *__restrict__ cand_g,
                                                             const uint32_t *__restrict__ cand_cum,
                                                             int32_t *__restrict__ topk_inst, int nbits,
-                                                            int chunk_tokens, int32_t *__restrict__ inst_hist, int I,
+                                                            int32_t *__restrict__ inst_hist, int I,
                                                             const int32_t *__restrict__ super_tot) {
-    __shared__ uint32_t cnt[GRACE_MAX_EXPERTS];
+    __shared__ int32_t cnt[GRACE_MAX_EXPERTS];                // requests of each expert before the current round
+    __shared__ int32_t wcnt[PICK_WAVES][GRACE_MAX_EXPERTS];   // per wavefront: match set sizes, then requests before it
     __shared__ int32_t s_ptr[GRACE_MAX_EXPERTS + 1];  // this view's candidate lists, offsets from its first entry
     __shared__ int32_t s_g[PICK_LDS_CANDS];
     __shared__ uint32_t s_cum[PICK_LDS_CANDS];
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int chunk = (int)blockIdx.x;
-    const int64_t a0 = (int64_t)chunk * chunk_tokens * k;
-    const int64_t a1 = min(n_assign, a0 + (int64_t)chunk_tokens * k);
-    // the first rounds' experts and the candidate table are fetched before the counters are
+    const int blk = (int)blockIdx.x;
+    const int64_t a0 = (int64_t)blk * PICK_TOKENS * k;
+    const int64_t a1 = min(n_assign, a0 + (int64_t)PICK_TOKENS * k);
+    const int row0 = blk * rows_per_block;  // first histogram row of this block's tokens
+    // the first round's experts and the candidate table are fetched before the counters are
     // prepared, so the picks below do not wait on chains of dependent global loads
-    int e_in[PICK_BATCH];
-    auto load_batch = [&](int64_t b0) {
-#pragma unroll
-        for (int q = 0; q < PICK_BATCH; ++q) {
-            const int64_t a = b0 + q * 64 + lane;
-            e_in[q] = a < a1 ? topk_expert[a] : -1;
-        }
-    };
-    if (wave == 0) load_batch(a0);
+    int e_first = (a0 + tid < a1) ? topk_expert[a0 + tid] : -1;
     const int c_first = cand_ptr[0], n_cand = cand_ptr[E] - c_first;
     const bool table_in_lds = n_cand <= PICK_LDS_CANDS;  // uniform
     if (table_in_lds) {
@@ -141,57 +144,67 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
         }
     }
     if (FOLD) {
-        // requests before this chunk: the wavefronts share the histogram rows 0 .. chunk-1, or, with
-        // super_tot, the super rows before the chunk's super-chunk and the chunk rows inside it
+        // requests before this block: the histogram rows 0 .. row0-1, or, with super_tot, the super
+        // rows before row0's super-chunk and the rows inside it
         for (int e = tid; e < E; e += PICK_THREADS) cnt[e] = 0;
         __syncthreads();
-        constexpr int NW = PICK_THREADS / 64;
         if (super_tot) {
-            const int s = chunk / FOLD_SUPER;
-            block_add_rows<NW>(super_tot, 0, s, E, (int32_t *)cnt, wave, lane);
-            block_add_rows<NW>(chunk_counts, s * FOLD_SUPER, chunk, E, (int32_t *)cnt, wave, lane);
+            const int s = row0 / FOLD_SUPER;
+            block_add_rows<PICK_THREADS>(super_tot, 0, s, E, cnt, tid);
+            block_add_rows<PICK_THREADS>(chunk_counts, s * FOLD_SUPER, row0, E, cnt, tid);
         } else {
-            block_add_rows<NW>(chunk_counts, 0, chunk, E, (int32_t *)cnt, wave, lane);
-        }
-        __syncthreads();
-        if (chunk == nchunks - 1) {
-            for (int e = tid; e < E; e += PICK_THREADS) {
-                const int32_t n = (int32_t)cnt[e] + chunk_counts[(size_t)chunk * E + e];
-                expert_count[e] = n;
-                if (rr_out) rr_out[e] = next_rr(rr_in, e, n, cand_ptr, cand_cum);
-            }
+            block_add_rows<PICK_THREADS>(chunk_counts, 0, row0, E, cnt, tid);
         }
     } else {
-        for (int e = tid; e < E; e += PICK_THREADS) cnt[e] = (uint32_t)chunk_counts[(size_t)chunk * E + e];
-        __syncthreads();
+        for (int e = tid; e < E; e += PICK_THREADS) cnt[e] = chunk_counts[(size_t)row0 * E + e];
     }
-    if (wave != 0) return;
-    // One wavefront walks the chunk in order.  Its LDS operations execute in program order, so a
-    // counter updated by the last lane of a match set is seen by the next group of 64 assignments
-    // (wave_ctr_* accesses, fenced per round).
     const int32_t *t_ptr = table_in_lds ? s_ptr : cand_ptr;
     const int32_t *t_g = table_in_lds ? s_g : cand_g;
     const uint32_t *t_cum = table_in_lds ? s_cum : cand_cum;
     const uint64_t lt = lanemask_lt();
-    for (int64_t b0 = a0; b0 < a1; b0 += PICK_BATCH * 64) {
-        if (b0 != a0) load_batch(b0);
+    const int ibits = bits_for(I);
+    static_assert(PERM_CHUNK % 64 == 0, "a wavefront's assignments must not straddle permutation chunks");
+    for (int64_t b0 = a0; b0 < a1; b0 += PICK_THREADS) {
+        const int64_t a = b0 + tid;
+        const int e_raw = (b0 == a0) ? e_first : (a < a1 ? topk_expert[a] : -1);
+        const bool valid = (unsigned)e_raw < (unsigned)E;  // -1 past the end
+        const int e = valid ? e_raw : 0;
+        for (int i = lane; i < E; i += 64) wcnt[wave][i] = 0;  // this wavefront's row; its LDS operations execute in order
+        const uint64_t same = wave_match((uint32_t)e, valid, nbits);
+        if (valid && is_last_of(same)) wcnt[wave][e] = (int32_t)__popcll(same);
+        __syncthreads();  // also orders the counters prepared above, or the previous round's, before the scan
+        for (int i = tid; i < E; i += PICK_THREADS) {
+            int32_t run = cnt[i];
 #pragma unroll
-        for (int q = 0; q < PICK_BATCH; ++q) {
-            if (b0 + q * 64 >= a1) break;  // uniform
-            const int64_t a = b0 + q * 64 + lane;
-            const int e_raw = e_in[q];
-            const bool valid = (unsigned)e_raw < (unsigned)E;  // -1 past the end of the chunk
-            const int e = valid ? e_raw : 0;
-            const uint64_t same = wave_match((uint32_t)e, valid, nbits);
-            if (valid) {
-                const uint32_t rank = (uint32_t)__popcll(same & lt);
-                const uint64_t c = (uint64_t)wave_ctr_load(&cnt[e]) + rank + (uint64_t)(rr_in ? rr_in[e] : 0u);
-                const int g = pick_candidate(c, e, t_ptr, t_g, t_cum);
-                topk_inst[a] = g;
-                if (inst_hist && (unsigned)g < (unsigned)I) atomicAdd(&inst_hist[(a / PERM_CHUNK) * I + g], 1);
+            for (int w = 0; w < PICK_WAVES; ++w) {
+                const int32_t c = wcnt[w][i];
+                wcnt[w][i] = run;
+                run += c;
             }
-            if (valid && is_last_of(same)) wave_ctr_add(&cnt[e], (uint32_t)__popcll(same));
-            wave_ctr_fence();
+            cnt[i] = run;
+        }
+        __syncthreads();
+        int g = 0;
+        if (valid) {
+            const uint64_t c = (uint64_t)(uint32_t)wcnt[wave][e] + (uint32_t)__popcll(same & lt) + (uint64_t)(rr_in ? rr_in[e] : 0u);
+            g = pick_candidate(c, e, t_ptr, t_g, t_cum);
+            topk_inst[a] = g;
+        }
+        if (inst_hist) {
+            // a wavefront's 64 assignments lie in one permutation chunk (both are multiples of 64):
+            // one atomic per distinct instance, by the highest lane of its match set
+            const bool counted = valid && (unsigned)g < (unsigned)I;
+            const uint64_t same_g = wave_match((uint32_t)g, counted, ibits);
+            if (counted && is_last_of(same_g)) atomicAdd(&inst_hist[(a / PERM_CHUNK) * I + g], (int32_t)__popcll(same_g));
+        }
+        __syncthreads();  // wcnt is cleared again in the next round
+    }
+    if (FOLD && blk == (int)gridDim.x - 1) {
+        // after its last round the last block's counters hold every request of the call
+        for (int e = tid; e < E; e += PICK_THREADS) {
+            const int32_t n = cnt[e];
+            expert_count[e] = n;
+            if (rr_out) rr_out[e] = next_rr(rr_in, e, n, cand_ptr, cand_cum);
         }
     }
 }
@@ -209,8 +222,11 @@ int launch_topk(const float *logits, int T, int E, int k, int renorm, int32_t *t
     if (chunk_tokens == ROUTE_CHUNK_SMALL)                                                                           \
         topk_kernel<VPL, ROUTE_CHUNK_SMALL / (TOPK_THREADS / 64)><<<nchunks, TOPK_THREADS, 0, st>>>(                \
             logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist, clear, n_clear);                          \
-    else                                                                                                             \
+    else if (chunk_tokens == ROUTE_CHUNK_LARGE)                                                                      \
         topk_kernel<VPL, ROUTE_CHUNK_LARGE / (TOPK_THREADS / 64)><<<nchunks, TOPK_THREADS, 0, st>>>(                \
+            logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist, clear, n_clear);                          \
+    else                                                                                                             \
+        topk_kernel<VPL, ROUTE_CHUNK_HUGE / (TOPK_THREADS / 64)><<<nchunks, TOPK_THREADS, 0, st>>>(                 \
             logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist, clear, n_clear)
     switch ((E + 63) / 64) {
         case 1: GRACE_TOPK(1); break;
@@ -267,6 +283,10 @@ int launch_route(const grace_table *table, int32_t local_rank, grace_policy poli
     }
     int nbits = 0;
     while ((1 << nbits) < E) ++nbits;
+    static_assert(PICK_TOKENS % ROUTE_CHUNK_SMALL == 0 && PICK_TOKENS % ROUTE_CHUNK_LARGE == 0 && PICK_TOKENS % ROUTE_CHUNK_HUGE == 0,
+                  "a pick block covers whole histogram rows");
+    const int rows_per_block = PICK_TOKENS / chunk_tokens;
+    const int pick_blocks = (int)ceil_div(T, PICK_TOKENS);
     const int mode = fold_mode(table, nchunks, E);
     if (mode != 0) {
         const int32_t *super_tot = nullptr;
@@ -275,9 +295,10 @@ int launch_route(const grace_table *table, int32_t local_rank, grace_policy poli
             GRACE_LAUNCH_CHECK("super_sum_kernel");
             super_tot = base;
         }
-        pick_kernel<true><<<nchunks, PICK_THREADS, 0, st>>>(topk_expert, (int64_t)T * k, E, k, hist, nchunks, rr_in, rr_out,
-                                                  expert_count, cand_ptr, table->d_cand_g, table->d_cand_cum, topk_inst,
-                                                  nbits, chunk_tokens, inst_hist, I, super_tot);
+        pick_kernel<true><<<pick_blocks, PICK_THREADS, 0, st>>>(topk_expert, (int64_t)T * k, E, k, hist, nchunks,
+                                                                rows_per_block, rr_in, rr_out, expert_count, cand_ptr,
+                                                                table->d_cand_g, table->d_cand_cum, topk_inst, nbits,
+                                                                inst_hist, I, super_tot);
         GRACE_LAUNCH_CHECK("pick_kernel");
         return GRACE_OK;
     }
@@ -285,9 +306,10 @@ int launch_route(const grace_table *table, int32_t local_rank, grace_policy poli
                                                   table->d_cand_cum);
     GRACE_LAUNCH_CHECK("route_scan_kernel");
     if (nchunks > 0) {
-        pick_kernel<false><<<nchunks, PICK_THREADS, 0, st>>>(topk_expert, (int64_t)T * k, E, k, base, nchunks, rr_in, rr_out,
-                                                   expert_count, cand_ptr, table->d_cand_g, table->d_cand_cum, topk_inst,
-                                                   nbits, chunk_tokens, inst_hist, I, nullptr);
+        pick_kernel<false><<<pick_blocks, PICK_THREADS, 0, st>>>(topk_expert, (int64_t)T * k, E, k, base, nchunks,
+                                                                 rows_per_block, rr_in, rr_out, expert_count, cand_ptr,
+                                                                 table->d_cand_g, table->d_cand_cum, topk_inst, nbits,
+                                                                 inst_hist, I, nullptr);
         GRACE_LAUNCH_CHECK("pick_kernel");
     }
     return GRACE_OK;

@@ -136,7 +136,12 @@ static __global__ __launch_bounds__(64) void key_pos_kernel(const int32_t *__res
 // chunks before its own), which saves the single-block scan launch; block 0 also writes the offset
 // outputs.  With super_tot (column sums per FOLD_SUPER chunk rows) the block reads the super rows
 // and the chunk rows of its own super-chunk instead of every row.
-constexpr int POS_FOLD_THREADS = 512;  // all eight wavefronts sum histogram rows; wavefront 0 scans and ranks
+// Ranking: with at most POS_PAR_KEYS keys every wavefront ranks 64 of the chunk's items at once
+// (match sets by ballot, their sizes in the wavefront's row of wcnt, an exclusive scan over the
+// eight rows on top of the chunk's start positions); with more keys wavefront 0 walks the chunk.
+constexpr int POS_FOLD_THREADS = 512, POS_WAVES = POS_FOLD_THREADS / 64;
+constexpr int POS_PAR_KEYS = 512;
+static_assert(PERM_CHUNK == POS_FOLD_THREADS, "one item per thread when all wavefronts rank");
 
 static __global__ __launch_bounds__(POS_FOLD_THREADS) void key_pos_fold_kernel(
     const int32_t *__restrict__ keys, int64_t n_items, int I, const int32_t *__restrict__ chunk_hist, int nchunks, int R,
@@ -146,79 +151,82 @@ static __global__ __launch_bounds__(POS_FOLD_THREADS) void key_pos_fold_kernel(
     const int32_t *__restrict__ super_tot) {
     __shared__ int32_t cnt[GRACE_MAX_INSTANCES];      // items of each key in the chunks before this one, then positions
     __shared__ int32_t off[GRACE_MAX_INSTANCES + 1];  // items of each key in all chunks, then exclusive offsets
+    __shared__ int32_t wcnt[POS_WAVES][POS_PAR_KEYS];
     const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int chunk = (int)blockIdx.x;
+    const bool par = I <= POS_PAR_KEYS;  // uniform
     int g[CHUNK_ROUNDS];
-    if (wave == 0) load_chunk_keys(keys, n_items, chunk, lane, g);  // in flight while the histograms are summed
+    int g_one = -1;
+    const int64_t a_one = (int64_t)chunk * PERM_CHUNK + tid;
+    if (par) g_one = a_one < n_items ? keys[a_one] : -1;          // in flight while the histograms are summed
+    else if (wave == 0) load_chunk_keys(keys, n_items, chunk, lane, g);
     for (int i = tid; i < I; i += POS_FOLD_THREADS) {
         cnt[i] = 0;
         off[i] = 0;
     }
     __syncthreads();
-    constexpr int NW = POS_FOLD_THREADS / 64;
     if (super_tot) {
         const int s = chunk / FOLD_SUPER, nsuper = (nchunks + FOLD_SUPER - 1) / FOLD_SUPER;
-        block_add_rows<NW>(super_tot, 0, nsuper, I, off, wave, lane);
-        block_add_rows<NW>(super_tot, 0, s, I, cnt, wave, lane);
-        block_add_rows<NW>(chunk_hist, s * FOLD_SUPER, chunk, I, cnt, wave, lane);
+        block_add_rows<POS_FOLD_THREADS>(super_tot, 0, nsuper, I, off, tid, cnt, s);
+        block_add_rows<POS_FOLD_THREADS>(chunk_hist, s * FOLD_SUPER, chunk, I, cnt, tid);
     } else {
-        // one pass over all rows gives both sums; (block of 64 keys, row) pairs are dealt to the
-        // wavefronts, each staying on one key block when the number of key blocks divides NW
-        const int nkb = (I + 63) / 64;
-        if (NW % nkb == 0) {
-            const int key = (wave % nkb) * 64 + lane, rstep = NW / nkb;
+        // one pass over all rows gives both sums
+        block_add_rows<POS_FOLD_THREADS>(chunk_hist, 0, nchunks, I, off, tid, cnt, chunk);
+    }
+    __syncthreads();
+    if (wave == 0) {
+        int32_t carry = 0;
+        for (int k0 = 0; k0 < I; k0 += 64) {
+            const int key = k0 + lane;
+            const int32_t tot = key < I ? off[key] : 0;
+            int32_t incl = tot;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int32_t v = __shfl_up(incl, o, 64);
+                if (lane >= o) incl += v;
+            }
             if (key < I) {
-                int32_t tot = 0, prev = 0;
-#pragma unroll 8
-                for (int c = wave / nkb; c < nchunks; c += rstep) {
-                    const int32_t v = chunk_hist[(size_t)c * I + key];
-                    tot += v;
-                    prev += (c < chunk) ? v : 0;
-                }
-                if (tot) atomicAdd(&off[key], tot);  // integer sums: order does not matter
-                if (prev) atomicAdd(&cnt[key], prev);
+                off[key] = carry + incl - tot;
+                cnt[key] += carry + incl - tot;
             }
-        } else {
-            for (int key = lane; key < I; key += 64) {
-                int32_t tot = 0, prev = 0;
-#pragma unroll 8
-                for (int c = wave; c < nchunks; c += NW) {
-                    const int32_t v = chunk_hist[(size_t)c * I + key];
-                    tot += v;
-                    prev += (c < chunk) ? v : 0;
-                }
-                if (tot) atomicAdd(&off[key], tot);
-                if (prev) atomicAdd(&cnt[key], prev);
-            }
+            carry += __shfl(incl, 63, 64);
+        }
+        if (lane == 0) off[I] = carry;
+        if (chunk == 0) {
+            for (int i = lane; i <= I; i += 64) inst_off[i] = off[i];
+            if (rank_off)
+                for (int r = lane; r <= R; r += 64) rank_off[r] = off[rank_ptr[r]];
+            if (node_off)
+                for (int n = lane; n <= N; n += 64) node_off[n] = off[node_first_inst[n]];
+        }
+        if (!par) rank_chunk(g, n_items, I, cnt, perm_pos, perm_src, nbits, src_div, chunk, lane);
+    }
+    if (!par) return;
+    // every wavefront ranks its 64 items: cnt[key] is the position of the chunk's first item with that key
+    const bool in = a_one < n_items;
+    const bool valid = in && (unsigned)g_one < (unsigned)I;
+    const int key = valid ? g_one : 0;
+    for (int i = lane; i < I; i += 64) wcnt[wave][i] = 0;  // this wavefront's row; its LDS operations execute in order
+    const uint64_t same = wave_match((uint32_t)key, valid, nbits);
+    if (valid && is_last_of(same)) wcnt[wave][key] = (int32_t)__popcll(same);
+    __syncthreads();  // also: wavefront 0 has finished cnt
+    for (int i = tid; i < I; i += POS_FOLD_THREADS) {
+        int32_t run = cnt[i];
+#pragma unroll
+        for (int w = 0; w < POS_WAVES; ++w) {
+            const int32_t c = wcnt[w][i];
+            wcnt[w][i] = run;
+            run += c;
         }
     }
     __syncthreads();
-    if (wave != 0) return;
-    int32_t carry = 0;
-    for (int k0 = 0; k0 < I; k0 += 64) {
-        const int key = k0 + lane;
-        const int32_t tot = key < I ? off[key] : 0;
-        int32_t incl = tot;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int32_t v = __shfl_up(incl, o, 64);
-            if (lane >= o) incl += v;
-        }
-        if (key < I) {
-            off[key] = carry + incl - tot;
-            cnt[key] += carry + incl - tot;
-        }
-        carry += __shfl(incl, 63, 64);
+    if (valid) {
+        const int32_t pos = wcnt[wave][key] + (int32_t)__popcll(same & lanemask_lt());
+        perm_pos[a_one] = pos;
+        perm_src[pos] = (int32_t)(a_one / src_div);  // src_div = 1: the item itself; k: its token
+    } else if (in) {
+        perm_pos[a_one] = -1;  // key outside the table: no row
     }
-    if (lane == 0) off[I] = carry;
-    if (chunk == 0) {
-        for (int i = lane; i <= I; i += 64) inst_off[i] = off[i];
-        if (rank_off)
-            for (int r = lane; r <= R; r += 64) rank_off[r] = off[rank_ptr[r]];
-        if (node_off)
-            for (int n = lane; n <= N; n += 64) node_off[n] = off[node_first_inst[n]];
-    }
-    rank_chunk(g, n_items, I, cnt, perm_pos, perm_src, nbits, src_div, chunk, lane);
 }
 
 // Host side: the launches of one stable counting sort.  hist / base: workspace of nchunks * nkeys

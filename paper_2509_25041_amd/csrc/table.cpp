@@ -228,6 +228,7 @@ int fold_mode(const grace_table *table, int nchunks, int nkeys) {
     constexpr int64_t SUPER = 64;  // rows per super-chunk (FOLD_SUPER of the kernels)
     const int64_t kb = (nkeys + 63) / 64;
     if (nchunks < 1) return 0;
+    if ((int64_t)nchunks * nkeys >= (int64_t)1 << 31) return 0;  // the folded sums index the histogram with 32 bits
     if (nchunks * kb <= table->fold_one_level) return 1;
     const int64_t nsuper = (nchunks + SUPER - 1) / SUPER;
     return (nsuper + SUPER) * kb <= table->fold_two_level ? 2 : 0;

@@ -71,28 +71,70 @@ __device__ __forceinline__ int bits_for(int nkeys) {
 }
 
 // Column sums of rows [r0, r1) of a row-major [rows][nkeys] int32 matrix, added into acc[nkeys] (LDS,
-// initialised by the caller) by a block of NW wavefronts.  The rows are dealt to the wavefronts; a
-// wavefront stays on one block of 64 keys when the number of key blocks divides NW.  Integer
-// atomics: the result is exact in any order.
-template <int NW>
-__device__ __forceinline__ void block_add_rows(const int32_t *__restrict__ m, int r0, int r1, int nkeys, int32_t *acc,
-                                               int wave, int lane) {
-    const int nkb = (nkeys + 63) / 64;
-    if (NW % nkb == 0) {
-        const int key = (wave % nkb) * 64 + lane, rstep = NW / nkb;
-        if (key < nkeys) {
-            int32_t part = 0;
+// initialised by the caller, who also synchronises before reading it) by a block of NT threads.
+// With `acc_lt` the rows below r_lt are also summed into acc_lt[nkeys].
+// The rows are read as a flat array in groups of whole rows of at most 4 * NT elements: a thread
+// reads four consecutive elements of every group (one 16-byte load where the alignment allows it),
+// always of the same four columns, so it sums in registers and adds to LDS once at the end; all
+// lanes are busy whatever nkeys is.  Integer sums: exact in any order.  `m` must be 16-byte aligned.
+template <int NT>
+__device__ __forceinline__ void block_add_rows(const int32_t *__restrict__ m, int r0, int r1, int nkeys, int32_t *acc, int tid,
+                                               int32_t *acc_lt = nullptr, int r_lt = 0) {
+    if (r1 <= r0) return;
+    const int rg = (4 * NT) / nkeys;  // rows per group
+    if (rg == 0) {
+        // rows longer than a group: a thread owns columns tid, tid + NT, ... and walks the rows
+        for (int key = tid; key < nkeys; key += NT) {
+            int32_t tot = 0, lt = 0;
 #pragma unroll 8
-            for (int r = r0 + wave / nkb; r < r1; r += rstep) part += m[(size_t)r * nkeys + key];
-            if (part) atomicAdd(&acc[key], part);
+            for (int r = r0; r < r1; ++r) {
+                const int32_t v = m[(size_t)r * nkeys + key];
+                tot += v;
+                lt += (r < r_lt) ? v : 0;
+            }
+            if (tot) atomicAdd(&acc[key], tot);
+            if (acc_lt && lt) atomicAdd(&acc_lt[key], lt);
         }
-    } else {
-        for (int key = lane; key < nkeys; key += 64) {
-            int32_t part = 0;
-#pragma unroll 8
-            for (int r = r0 + wave; r < r1; r += NW) part += m[(size_t)r * nkeys + key];
-            if (part) atomicAdd(&acc[key], part);
+        return;
+    }
+    const int gs = rg * nkeys;        // elements per group, <= 4 * NT
+    const int o = 4 * tid;            // this thread's elements of a group: o .. o + 3
+    if (o >= gs) return;
+    int key[4], row[4];
+    bool on[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        on[q] = o + q < gs;
+        row[q] = (o + q) / nkeys;
+        key[q] = (o + q) - row[q] * nkeys;
+    }
+    const int64_t s0 = (int64_t)r0 * nkeys, s1 = (int64_t)r1 * nkeys;
+    const bool vec = (s0 % 4 == 0) && (gs % 4 == 0);  // then every group start and o are multiples of four elements
+    const int ngroups = (r1 - r0 + rg - 1) / rg;
+    int32_t tot[4] = {0, 0, 0, 0}, lt[4] = {0, 0, 0, 0};
+#pragma unroll 4
+    for (int grp = 0; grp < ngroups; ++grp) {
+        const int64_t f = s0 + (int64_t)grp * gs + o;  // flat index of this thread's first element
+        int32_t v[4] = {0, 0, 0, 0};
+        if (vec && f + 3 < s1) {
+            const uint4 x = *(const uint4 *)(m + f);
+            v[0] = (int32_t)x.x; v[1] = (int32_t)x.y; v[2] = (int32_t)x.z; v[3] = (int32_t)x.w;
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (on[q] && f + q < s1) v[q] = m[f + q];
         }
+        const int rbase = r0 + grp * rg;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            tot[q] += v[q];
+            lt[q] += (rbase + row[q] < r_lt) ? v[q] : 0;
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (on[q] && tot[q]) atomicAdd(&acc[key[q]], tot[q]);
+        if (acc_lt && on[q] && lt[q]) atomicAdd(&acc_lt[key[q]], lt[q]);
     }
 }
 
@@ -107,7 +149,7 @@ static __global__ __launch_bounds__(SUPER_THREADS) void super_sum_kernel(const i
     const int tid = (int)threadIdx.x, s = (int)blockIdx.x;
     for (int i = tid; i < nkeys; i += SUPER_THREADS) acc[i] = 0;
     __syncthreads();
-    block_add_rows<SUPER_THREADS / 64>(hist, s * FOLD_SUPER, min(nchunks, (s + 1) * FOLD_SUPER), nkeys, acc, tid >> 6, tid & 63);
+    block_add_rows<SUPER_THREADS>(hist, s * FOLD_SUPER, min(nchunks, (s + 1) * FOLD_SUPER), nkeys, acc, tid);
     __syncthreads();
     for (int i = tid; i < nkeys; i += SUPER_THREADS) super_tot[(size_t)s * nkeys + i] = acc[i];
 }
