@@ -99,6 +99,7 @@ struct grace_table {
     void *d_base = nullptr;
     // per (local_rank, expert): candidates of the tier Algorithm 4 selects
     const int32_t *d_cand_ptr = nullptr;   // [(R+1)*E + 1]; block R = all instances (no locality)
+    std::vector<int32_t> cand_view;        // host: cand_ptr[v * E] for v = 0 .. R+1 (first candidate of each view)
     const int32_t *d_cand_g = nullptr;     // instance id of each candidate, ascending rank
     const uint32_t *d_cand_cum = nullptr;  // inclusive cumulative polling weight inside the tier
     const int32_t *d_rank_ptr = nullptr;   // [R+1]

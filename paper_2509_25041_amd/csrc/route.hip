@@ -120,7 +120,8 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
                                                             const uint32_t *__restrict__ cand_cum,
                                                             int32_t *__restrict__ topk_inst, int nbits,
                                                             int32_t *__restrict__ inst_hist, int I,
-                                                            const int32_t *__restrict__ super_tot) {
+                                                            const int32_t *__restrict__ super_tot, int c_first,
+                                                            int n_cand) {
     __shared__ int32_t cnt[GRACE_MAX_EXPERTS];                // requests of each expert before the current round
     __shared__ int32_t wcnt[PICK_WAVES][GRACE_MAX_EXPERTS];   // per wavefront: match set sizes, then requests before it
     __shared__ int32_t s_ptr[GRACE_MAX_EXPERTS + 1];  // this view's candidate lists, offsets from its first entry
@@ -134,7 +135,8 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
     // the first round's experts and the candidate table are fetched before the counters are
     // prepared, so the picks below do not wait on chains of dependent global loads
     int e_first = (a0 + tid < a1) ? topk_expert[a0 + tid] : -1;
-    const int c_first = cand_ptr[0], n_cand = cand_ptr[E] - c_first;
+    // c_first = cand_ptr[0], n_cand = cand_ptr[E] - c_first: known to the host, so the staging loads
+    // below do not wait for them
     const bool table_in_lds = n_cand <= PICK_LDS_CANDS;  // uniform
     if (table_in_lds) {
         for (int i = tid; i <= E; i += PICK_THREADS) s_ptr[i] = cand_ptr[i] - c_first;
@@ -275,7 +277,9 @@ int launch_route(const grace_table *table, int32_t local_rank, grace_policy poli
     const int I = table->I;
     int32_t *hist = (int32_t *)ws;
     int32_t *base = (int32_t *)((char *)ws + align_up((size_t)nchunks * E * 4, 256));
-    const int32_t *cand_ptr = table->d_cand_ptr + (size_t)(policy == GRACE_POLICY_WRR ? table->R : local_rank) * E;
+    const int view = policy == GRACE_POLICY_WRR ? table->R : local_rank;
+    const int32_t *cand_ptr = table->d_cand_ptr + (size_t)view * E;
+    const int c_first = table->cand_view[view], n_cand = table->cand_view[view + 1] - c_first;
     if (nchunks > 0) {
         const int64_t n_clear = inst_hist ? ceil_div((int64_t)T * k, PERM_CHUNK) * I : 0;
         const int rc_topk = launch_topk(logits, T, E, k, renorm, topk_expert, topk_weight, hist, inst_hist, (int)n_clear, st);
@@ -298,7 +302,7 @@ int launch_route(const grace_table *table, int32_t local_rank, grace_policy poli
         pick_kernel<true><<<pick_blocks, PICK_THREADS, 0, st>>>(topk_expert, (int64_t)T * k, E, k, hist, nchunks,
                                                                 rows_per_block, rr_in, rr_out, expert_count, cand_ptr,
                                                                 table->d_cand_g, table->d_cand_cum, topk_inst, nbits,
-                                                                inst_hist, I, super_tot);
+                                                                inst_hist, I, super_tot, c_first, n_cand);
         GRACE_LAUNCH_CHECK("pick_kernel");
         return GRACE_OK;
     }
@@ -309,7 +313,7 @@ int launch_route(const grace_table *table, int32_t local_rank, grace_policy poli
         pick_kernel<false><<<pick_blocks, PICK_THREADS, 0, st>>>(topk_expert, (int64_t)T * k, E, k, base, nchunks,
                                                                  rows_per_block, rr_in, rr_out, expert_count, cand_ptr,
                                                                  table->d_cand_g, table->d_cand_cum, topk_inst, nbits,
-                                                                 inst_hist, I, nullptr);
+                                                                 inst_hist, I, nullptr, c_first, n_cand);
         GRACE_LAUNCH_CHECK("pick_kernel");
     }
     return GRACE_OK;

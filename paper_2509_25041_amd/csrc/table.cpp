@@ -155,6 +155,8 @@ extern "C" int grace_table_create(grace_table **out, int32_t E, int32_t R, int32
     const size_t total = o_rnode + al((size_t)R * 4);
     std::vector<char> stage(total, 0);
     memcpy(stage.data() + o_ptr, cand_ptr.data(), cand_ptr.size() * 4);
+    t->cand_view.resize((size_t)R + 2);
+    for (int v = 0; v <= R + 1; ++v) t->cand_view[v] = cand_ptr[(size_t)v * E];
     memcpy(stage.data() + o_g, cand_g.data(), cand_g.size() * 4);
     memcpy(stage.data() + o_cum, cand_cum.data(), cand_cum.size() * 4);
     memcpy(stage.data() + o_rank, t->rank_ptr.data(), (size_t)(R + 1) * 4);
