@@ -30,7 +30,7 @@ ROTATE_BELOW_BYTES = 256 << 20   # Infinity Cache: smaller working sets are also
 KERNEL_OF_STAGE = {
     "ffn_up": "gemm_bf16_persist_kernel<true, *, EXPERTS> (grouped gate+up projection, fused SwiGLU)",
     "ffn_down": "gemm_bf16_persist_kernel<false, *, EXPERTS> (grouped down projection)",
-    "shared_up": "gemm_bf16_persist_kernel<true, 1, SHARED> (shared experts' gate+up projection, fused SwiGLU)",
+    "shared_up": "gemm_bf16_persist_kernel<true, 1, SHARED> (shared experts' gate+up projection, fused SwiGLU; carries the row scatter)",
     "shared_down": "gemm_bf16_persist_kernel<false, 1, SHARED> (shared experts' down projection)",
     "combine": "combine_kernel (weighted gather to token order)",
     "route_permute": "topk + pick + positions + scatter_rows_kernel (one call; the row scatter moves the bytes)",
@@ -164,11 +164,15 @@ def run_workload(name: str, steps: int, warmup: int, rotate: int = 0, mfma_probe
     bytes_route = T * (4 * cfg.E + 12 * k)
     bytes_permute = T * d * el + T * k * d * el + 12 * T * k
     bytes_combine = T * k * d * el + T * d * el * (2 if sh is not None else 1) + 8 * T * k
+    # with shared experts the row scatter rides on the shared gate+up projection's launch: the dispatch call
+    # then builds only the index arrays
+    fused_scatter = bool(getattr(layer, "fuse_scatter", False)) and sh is not None
+    bytes_dispatch = bytes_route + (12 * T * k if fused_scatter else bytes_permute)
     # algorithmic work per launch of the kernel behind each call: (bound, amount, unit scale, peak)
     work = {
         "ffn_up": ("mfma", 4.0 * d * f * m_loc), "ffn_down": ("mfma", 2.0 * d * f * m_loc),
         "shared_up": ("mfma", 4.0 * d * f * cfg.n_shared * T), "shared_down": ("mfma", 2.0 * d * f * cfg.n_shared * T),
-        "combine": ("hbm", float(bytes_combine)), "route_permute": ("hbm", float(bytes_route + bytes_permute)),
+        "combine": ("hbm", float(bytes_combine)), "route_permute": ("hbm", float(bytes_dispatch)),
     }
 
     def achieved(stage, ms):
@@ -258,10 +262,11 @@ def run_workload(name: str, steps: int, warmup: int, rotate: int = 0, mfma_probe
         if s in work:
             a, p, u = achieved(s, stage_ms[s])
             stages_achieved[s] = {"achieved": a, "unit": u, "frac": a / p}
-    t_hbm = stage_ms.get("combine", 0.0) + stage_ms.get("route_permute", 0.0)
-    stages_achieved["route_permute_combine"] = {
-        "achieved": (bytes_route + bytes_permute + bytes_combine) / (t_hbm * 1e-3) / 1e9, "unit": "GB/s",
-        "frac": (bytes_route + bytes_permute + bytes_combine) / (t_hbm * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    if not fused_scatter:
+        t_hbm = stage_ms.get("combine", 0.0) + stage_ms.get("route_permute", 0.0)
+        stages_achieved["route_permute_combine"] = {
+            "achieved": (bytes_route + bytes_permute + bytes_combine) / (t_hbm * 1e-3) / 1e9, "unit": "GB/s",
+            "frac": (bytes_route + bytes_permute + bytes_combine) / (t_hbm * 1e-3) / 1e9 / PEAK_HBM_GBS}
     result = {
         "ms_per_step": ms_per_step,
         "tokens_per_s": T / (ms_per_step * 1e-3),
@@ -270,7 +275,8 @@ def run_workload(name: str, steps: int, warmup: int, rotate: int = 0, mfma_probe
                                f"ranks, local rank {lr}, Zipf s={cfg.zipf_s}, {cfg.n_shared} shared experts",
                    "local_rows": m_loc, "local_slots": int(len(experts)),
                    "rows_per_slot_min_max": [int(seg.min()), int(seg.max())] if len(seg) else [0, 0],
-                   "n_shared": cfg.n_shared, "working_set_MB": ws_bytes / 1e6},
+                   "n_shared": cfg.n_shared, "working_set_MB": ws_bytes / 1e6,
+                   "row_scatter": "carried by the shared gate+up projection's launch" if fused_scatter else "in the dispatch call"},
         "roofline": {"kernel": KERNEL_OF_STAGE[dominant] if cfg.dtype == "bf16" else f"{dominant} (fp32 FMA path)",
                      "stage": dominant, "bound": work[dominant][0], "achieved": ach, "peak": peak, "unit": unit,
                      "frac": ach / peak, "traffic": traffic, "avg_launch_ms": dom_ms,

@@ -175,6 +175,14 @@ int grace_permute(const grace_table *table, const int32_t *topk_inst, int32_t T,
                   grace_dtype dt, int32_t *perm_pos, int32_t *perm_src, int32_t *inst_off, int32_t *rank_off,
                   int32_t *node_off, void *xp, void *ws, void *stream);
 
+/* The row movement of grace_permute alone (Section 5: rows in dispatch order), for callers that
+ * built the index arrays with x == NULL and move the rows later or on another stream:
+ *     xp[perm_pos[t*k+j]] = x[t]   for every assignment whose perm_pos is in [0, T*k).
+ * DEVICE: x [T,d]; perm_pos [T*k] from grace_permute / grace_route_permute; xp [T*k,d].
+ * Limits as for grace_permute with x != NULL. */
+int grace_permute_rows(const void *x, const int32_t *perm_pos, int32_t T, int32_t k, int32_t d, grace_dtype dt, void *xp,
+                       void *stream);
+
 /* ---- grace_route_permute: grace_route then grace_permute in one call ----------
  * Same arguments, outputs (bit for bit) and errors as grace_route (Section 3,
  * Section 4.3, Algorithms 3 and 4) followed by grace_permute (Section 5) on its
@@ -308,6 +316,18 @@ int grace_shared_ffn_up(const void *x, int32_t T, int32_t d, int32_t f, int32_t 
                         const void *w_gate, const void *w_up, void *ws, void *stream);
 int grace_shared_ffn_down(int32_t T, int32_t d, int32_t f, int32_t n_shared, grace_dtype dt, const void *w_down,
                           void *y_shared, void *ws, void *stream);
+
+/* grace_shared_ffn_up and grace_permute_rows (the row movement of Section 5's dispatch order) as one
+ * call: both read only x (and perm_pos), the projection is bound by the matrix cores and the row
+ * movement by HBM, so for bf16 rows that are multiples of 1024 bytes the persistent kernel of the
+ * projection carries the rows along (every wavefront moves a 1 KB piece of a token row every few K
+ * steps) instead of a launch of its own; other shapes run the two launches.  Outputs are those of the
+ * two calls, bit for bit: the hidden activation in ws and xp[perm_pos[t*k+j]] = x[t].
+ * DEVICE: perm_pos [T*k] from grace_permute / grace_route_permute called with x == NULL; xp [T*k,d];
+ * the rest as for grace_shared_ffn_up.  xp must not overlap x or ws. */
+int grace_shared_ffn_up_scatter(const void *x, int32_t T, int32_t d, int32_t f, int32_t n_shared, grace_dtype dt,
+                                const void *w_gate, const void *w_up, void *ws, const int32_t *perm_pos, int32_t k,
+                                void *xp, void *stream);
 
 /* ---- grace_combine: weighted aggregation back to token order ----------------
  * The aggregation step that follows the expert computation (Section 1):

@@ -23,11 +23,13 @@ from .binding import (  # noqa: F401
     grace_last_error,
     grace_mfma_sustained,
     grace_permute,
+    grace_permute_rows,
     grace_route,
     grace_route_permute,
     grace_route_permute_static,
     grace_send_lists,
     grace_shared_ffn,
+    grace_shared_ffn_up_scatter,
     grace_table_validate,
     grace_workspace_bytes,
     library_path,

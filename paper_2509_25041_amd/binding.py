@@ -19,9 +19,9 @@ _STATUS = {0: "GRACE_OK", -1: "GRACE_EINVAL", -2: "GRACE_ESHAPE", -3: "GRACE_ETA
 EXPORTS = ("grace_table_validate", "grace_table_create", "grace_table_destroy", "grace_table_info",
            "grace_table_instances", "grace_table_local_experts", "grace_table_set_fold_limits", "grace_workspace_bytes",
            "grace_route",
-           "grace_permute", "grace_route_permute", "grace_route_permute_static", "grace_send_lists", "grace_expert_ffn", "grace_expert_ffn_up",
+           "grace_permute", "grace_permute_rows", "grace_route_permute", "grace_route_permute_static", "grace_send_lists", "grace_expert_ffn", "grace_expert_ffn_up",
            "grace_expert_ffn_down", "grace_expert_ffn_up_share", "grace_expert_ffn_down_share",
-           "grace_shared_ffn", "grace_shared_ffn_up", "grace_shared_ffn_down", "grace_combine", "grace_mfma_sustained",
+           "grace_shared_ffn", "grace_shared_ffn_up", "grace_shared_ffn_down", "grace_shared_ffn_up_scatter", "grace_combine", "grace_mfma_sustained",
            "grace_last_error")
 
 _lib: Optional[C.CDLL] = None
@@ -61,6 +61,7 @@ def load_library() -> C.CDLL:
     lib.grace_workspace_bytes.argtypes = [i32] * 7 + [C.c_int]
     lib.grace_route.argtypes = [vp, i32, C.c_int, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.grace_permute.argtypes = [vp, vp, i32, i32, vp, i32, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.grace_permute_rows.argtypes = [vp, vp, i32, i32, i32, C.c_int, vp, vp]
     lib.grace_route_permute.argtypes = [vp, i32, C.c_int, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp,
                                         vp, i32, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.grace_route_permute_static.argtypes = [vp, i32, C.c_int, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp,
@@ -73,6 +74,7 @@ def load_library() -> C.CDLL:
     lib.grace_expert_ffn_down_share.argtypes = [vp, i32, vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp]
     lib.grace_shared_ffn.argtypes = [vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp, vp, vp]
     lib.grace_shared_ffn_up.argtypes = [vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp]
+    lib.grace_shared_ffn_up_scatter.argtypes = [vp, i32, i32, i32, i32, C.c_int, vp, vp, vp, vp, i32, vp, vp]
     lib.grace_shared_ffn_down.argtypes = [i32, i32, i32, i32, C.c_int, vp, vp, vp, vp]
     lib.grace_combine.argtypes = [vp, vp, vp, i32, i32, i32, C.c_int, vp, vp, vp]
     lib.grace_mfma_sustained.argtypes = [i32, i32, C.POINTER(C.c_double), vp]
@@ -372,6 +374,25 @@ def grace_shared_ffn(x: torch.Tensor, w_gate: torch.Tensor, w_up: torch.Tensor, 
     _check(load_library().grace_shared_ffn(_dp(x), T, d, f, n_shared, dt, _dp(w_gate), _dp(w_up), _dp(w_down),
                                            _dp(y_shared), _dp(ws), _stream()))
     return y_shared
+
+
+def grace_permute_rows(x: torch.Tensor, perm_pos: torch.Tensor, k: int, xp: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The row movement of grace_permute alone: xp[perm_pos[t*k+j]] = x[t]; see grace_moe.h."""
+    T, d = x.shape
+    if xp is None:
+        xp = torch.empty((T * k, d), dtype=x.dtype, device=x.device)
+    _check(load_library().grace_permute_rows(_dp(x), _dp(perm_pos), T, k, d, _dtype_code(x), _dp(xp), _stream()))
+    return xp
+
+
+def grace_shared_ffn_up_scatter(x: torch.Tensor, w_gate: torch.Tensor, w_up: torch.Tensor, ws: torch.Tensor,
+                                perm_pos: torch.Tensor, k: int, xp: torch.Tensor) -> None:
+    """grace_shared_ffn_up (hidden activation into ws) and grace_permute_rows (rows into xp) as one call; see
+    grace_moe.h."""
+    T, d = x.shape
+    n_shared, f, _ = w_gate.shape
+    _check(load_library().grace_shared_ffn_up_scatter(_dp(x), T, d, f, n_shared, _dtype_code(x), _dp(w_gate), _dp(w_up),
+                                                      _dp(ws), _dp(perm_pos), k, _dp(xp), _stream()))
 
 
 def grace_combine(y: torch.Tensor, perm_pos: torch.Tensor, topk_weight: torch.Tensor,

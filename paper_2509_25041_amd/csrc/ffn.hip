@@ -216,14 +216,15 @@ static int shared_ffn_common(const char *who, int32_t T, int32_t d, int32_t f, i
 // The shared experts act as one expert of width F = n_shared * f: gate and up weights [n_shared, f, d]
 // are one [F, d] matrix each; the down weights [n_shared, d, f] are F input features in n_shared
 // K segments of length f that lie d * f elements apart.
-extern "C" int grace_shared_ffn_up(const void *x, int32_t T, int32_t d, int32_t f, int32_t n_shared, grace_dtype dt,
-                                   const void *w_gate, const void *w_up, void *ws, void *stream) {
-    int rc = shared_ffn_common("shared_ffn_up", T, d, f, n_shared, dt);
+static int shared_ffn_up(const char *who, const void *x, int32_t T, int32_t d, int32_t f, int32_t n_shared, grace_dtype dt,
+                         const void *w_gate, const void *w_up, void *ws, const int32_t *perm_pos, int32_t k, void *xp,
+                         void *stream) {
+    int rc = shared_ffn_common(who, T, d, f, n_shared, dt);
     if (rc != GRACE_OK) return rc;
     if (T == 0) return GRACE_OK;
-    if (!x || !w_gate || !w_up || !ws) return fail(GRACE_EINVAL, "shared_ffn_up: null device pointer");
+    if (!x || !w_gate || !w_up || !ws) return fail(GRACE_EINVAL, "%s: null device pointer", who);
     if ((((uintptr_t)x) | ((uintptr_t)w_gate) | ((uintptr_t)w_up) | ((uintptr_t)ws)) & 15)
-        return fail(GRACE_EINVAL, "shared_ffn_up: device pointers must be 16-byte aligned");
+        return fail(GRACE_EINVAL, "%s: device pointers must be 16-byte aligned", who);
     const int F = n_shared * f;
     GemmArgs up{};
     up.A = x; up.lda = d;
@@ -231,7 +232,34 @@ extern "C" int grace_shared_ffn_up(const void *x, int32_t T, int32_t d, int32_t 
     up.N = F; up.K = d; up.kseg_len = d; up.kseg_stride = 0;
     up.out = ws; up.ldo = F;
     up.seg_off = nullptr; up.S = 1; up.M_single = T;
-    return launch_gemm<true, pers::SHARED>(up, dt, T, (hipStream_t)stream, "shared_ffn up projection");
+    if (perm_pos) {
+        // the row scatter rides on the persistent bf16 kernel when rows are whole 1 KB pieces; otherwise it
+        // is a launch of its own ahead of the projection
+        const size_t row_bytes = (size_t)d * (dt == GRACE_F32 ? 4 : 2);
+        const bool persistent = dt == GRACE_BF16 && d % pers::BK == 0 && d >= pers::MIN_K_STEPS * pers::BK;
+        if (persistent && row_bytes % 1024 == 0 && (int64_t)T * k < ((int64_t)1 << 29) && row_bytes <= (size_t)INT32_MAX) {
+            up.sc_x = x; up.sc_xp = xp; up.sc_pos = perm_pos; up.sc_T = T; up.sc_k = k; up.sc_row_bytes = (int)row_bytes;
+        } else {
+            rc = grace_permute_rows(x, perm_pos, T, k, d, dt, xp, stream);
+            if (rc != GRACE_OK) return rc;
+        }
+    }
+    return launch_gemm<true, pers::SHARED>(up, dt, T, (hipStream_t)stream, who);
+}
+
+extern "C" int grace_shared_ffn_up(const void *x, int32_t T, int32_t d, int32_t f, int32_t n_shared, grace_dtype dt,
+                                   const void *w_gate, const void *w_up, void *ws, void *stream) {
+    return shared_ffn_up("shared_ffn_up", x, T, d, f, n_shared, dt, w_gate, w_up, ws, nullptr, 0, nullptr, stream);
+}
+
+extern "C" int grace_shared_ffn_up_scatter(const void *x, int32_t T, int32_t d, int32_t f, int32_t n_shared, grace_dtype dt,
+                                           const void *w_gate, const void *w_up, void *ws, const int32_t *perm_pos,
+                                           int32_t k, void *xp, void *stream) {
+    if (k < 1) return fail(GRACE_EINVAL, "shared_ffn_up_scatter: k=%d invalid", k);
+    if (T > 0 && (!perm_pos || !xp)) return fail(GRACE_EINVAL, "shared_ffn_up_scatter: null device pointer");
+    if (((uintptr_t)xp) & 15) return fail(GRACE_EINVAL, "shared_ffn_up_scatter: xp must be 16-byte aligned");
+    if ((int64_t)T * k > INT32_MAX) return fail(GRACE_ESHAPE, "shared_ffn_up_scatter: T*k exceeds 2^31-1");
+    return shared_ffn_up("shared_ffn_up_scatter", x, T, d, f, n_shared, dt, w_gate, w_up, ws, perm_pos, k, xp, stream);
 }
 
 extern "C" int grace_shared_ffn_down(int32_t T, int32_t d, int32_t f, int32_t n_shared, grace_dtype dt,

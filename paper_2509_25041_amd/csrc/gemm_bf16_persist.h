@@ -84,7 +84,12 @@ __device__ __forceinline__ int swizzle_key(int row) { return (row >> 1) & (CPR -
 // not count the load against the LDS counter, and the fragment reads around it keep their exact
 // per-read waits instead of "wait for everything".  The waits for these loads are explicit
 // s_waitcnt vmcnt(N) in the K loop.  M0 is written here only: nothing else in these kernels
-// needs it (LDS instructions do not on this target).
+// needs it (LDS instructions do not on this target).  The compiler does not see inside the assembly and
+// cannot keep the hardware's wait states for it: s_nop 0 is the one between the write of M0 and its
+// use; the five wait states between a VECTOR instruction writing `base` (a v_readlane that reloads
+// a spilled pointer) and the load reading it are not padded here (three more idle cycles per load cost
+// 0.5-1 % of the kernel): `base` is kept by scalar instructions, and asm_hazards.py / its test verify on
+// the compiled ISA that no such write comes closer than that to any assembly block.
 __device__ __forceinline__ void load16_to_lds(const char *base, uint32_t voff, char *lds_wave_base) {
     const uint32_t lds_addr = (uint32_t)(size_t)(__attribute__((address_space(3))) char *)lds_wave_base;
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0" ::"s"(base), "v"(voff), "s"(lds_addr) : "memory");
@@ -153,15 +158,6 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     if (WHO == EXPERTS) {
         if (FUSED_UP) share_record(g); else share_clear_stale(g);
     }
-    int job = bslot;
-    if (job >= njobs) return;
-
-    const int nk = g.K / BK;
-
-    // ---- load sources: a scalar base per operand (advancing along K) + a 32-bit byte offset per lane ----
-    // One wavefront-wide load fills 1 KB of LDS = ROWS_PER_LOAD consecutive tile rows; lane l
-    // lands at row l / CPR, chunk position l % CPR.  Loads 0, 1 of the fused weight tile read the
-    // gate matrix, loads 2, 3 the up matrix (tile rows 128 .. 255).
     // Lane-dependent values that are only needed at tile boundaries are recomputed there from an
     // opaque copy of the lane id: kept live across the K loop they would be spilled to scratch.
     auto opaque_lane = [&]() {
@@ -169,6 +165,93 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
         asm volatile("" : "+v"(l));
         return l;
     };
+    // ---- row scatter carried along (shared experts' gate+up projection only) ---------------------
+    // The kernel is bound by the matrix cores and leaves most of the HBM bandwidth unused, the row
+    // scatter of the dispatch permutation is bound by HBM and leaves the matrix cores idle, and the
+    // two are independent.  Every wavefront therefore moves SC_NU 1 KB pieces of token rows every
+    // SC_PERIOD-th K step: the pieces and their tokens' k positions are loaded just before a K step (so they are
+    // older than the step's four weight loads and have landed when the step's wait has passed) and
+    // stored to the k rows right after it.  Pieces are dealt round-robin to all wavefronts of the grid;
+    // whatever is left when a wavefront runs out of K steps is moved at the end, so the scatter is
+    // complete whatever the tile count.
+    constexpr bool COPY = FUSED_UP && WHO == SHARED;
+    const bool copy_on = COPY && g.sc_x != nullptr;                       // uniform
+    const int sc_cpr = copy_on ? g.sc_row_bytes / 1024 : 1;                // 1 KB pieces per row
+    const int sc_units = copy_on ? g.sc_T * sc_cpr : 0;
+    const int sc_stride = (int)gridDim.x * (THREADS / 64);
+    int sc_u = (int)blockIdx.x * (THREADS / 64) + wave;                    // this wavefront's next piece
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    // Measured on the 32768-token workload (k = 6): one piece every 4th step, all wavefronts at the same
+    // steps, adds 83 us to the 577 us projection for a 188 us scatter; four pieces every 16th step cost
+    // 30 us more than that, the wavefronts taking turns (some wavefront storing in every step) 40 us
+    // more, plain instead of non-temporal stores 20 us more.
+    constexpr int SC_NU = 1;                                               // pieces per copy event
+    constexpr int SC_PERIOD = 4 * SC_NU;                                   // K steps between copy events
+    u32x4_t sc_data[SC_NU];
+    int sc_pos_v[SC_NU], sc_q[SC_NU];
+    int sc_pending = 0;                                                    // pieces loaded and not yet stored (uniform)
+#pragma unroll
+    for (int n = 0; n < SC_NU; ++n) {
+        sc_data[n] = u32x4_t{0u, 0u, 0u, 0u};
+        sc_pos_v[n] = 0;
+        sc_q[n] = 0;
+    }
+    auto copy_issue = [&]() {
+        if (!copy_on) return;
+        const int ll = opaque_lane();
+#pragma unroll
+        for (int n = 0; n < SC_NU; ++n) {
+            if (sc_u >= sc_units) break;
+            const int t = sc_u / sc_cpr;
+            sc_q[n] = sc_u - t * sc_cpr;
+            const uint32_t poff = (uint32_t)(t * g.sc_k + min(ll, g.sc_k - 1)) * 4u;   // T*k < 2^29 here (launcher)
+            const char *src = (const char *)g.sc_x + (int64_t)t * g.sc_row_bytes + sc_q[n] * 1024;
+            // s_nop 4: the compiler does not see inside inline assembly, so it cannot keep the five wait
+            // states between a vector instruction that wrote one of these scalar registers (a v_readlane
+            // that reloads a spilled pointer, say) and the memory instruction that reads it
+            asm volatile("s_nop 4\n\tglobal_load_dword %0, %2, %3\n\tglobal_load_dwordx4 %1, %4, %5"
+                         : "=&v"(sc_pos_v[n]), "=&v"(sc_data[n])
+                         : "v"(poff), "s"(g.sc_pos), "v"((uint32_t)ll * 16u), "s"(src)
+                         : "memory");
+            sc_pending = n + 1;
+            sc_u += sc_stride;
+        }
+    };
+    auto copy_store = [&]() {   // only after a wait that covers the loads of copy_issue
+        if (sc_pending == 0) return;
+        const uint32_t voff = (uint32_t)opaque_lane() * 16u;
+        const int64_t n_rows = (int64_t)g.sc_T * g.sc_k;
+#pragma unroll
+        for (int n = 0; n < SC_NU; ++n) {
+            if (n >= sc_pending) break;
+            for (int j = 0; j < g.sc_k; ++j) {
+                const int p = __builtin_amdgcn_readlane(sc_pos_v[n], j);
+                if (p < 0 || p >= n_rows) continue;
+                char *dst = (char *)g.sc_xp + (int64_t)p * g.sc_row_bytes + sc_q[n] * 1024;
+                asm volatile("s_nop 4\n\tglobal_store_dwordx4 %0, %1, %2 nt" ::"v"(voff), "v"(sc_data[n]), "s"(dst) : "memory");
+            }
+        }
+        sc_pending = 0;
+    };
+    auto copy_rest = [&]() {
+        while (copy_on && sc_u < sc_units) {
+            copy_issue();
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            copy_store();
+        }
+    };
+    int job = bslot;
+    if (job >= njobs) {
+        if (COPY) copy_rest();
+        return;
+    }
+
+    const int nk = g.K / BK;
+
+    // ---- load sources: a scalar base per operand (advancing along K) + a 32-bit byte offset per lane ----
+    // One wavefront-wide load fills 1 KB of LDS = ROWS_PER_LOAD consecutive tile rows; lane l
+    // lands at row l / CPR, chunk position l % CPR.  Loads 0, 1 of the fused weight tile read the
+    // gate matrix, loads 2, 3 the up matrix (tile rows 128 .. 255).
     const char *a_ptr = nullptr, *b_ptr0 = nullptr, *b_ptr1 = nullptr;  // uniform
     uint32_t a_voff[LOADS], b_voff[LOADS];
     int kpos = 0;
@@ -455,7 +538,12 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
 #pragma unroll
                     for (int v = 0; v < 16; ++v) acc[i][jj][v] = 0.0f;
             fetch(0, smem + a_con * A_BYTES, smem + B_BASE + b_con * B_BYTES, 0);
-            for (int kt = 0; kt + 2 < nk; ++kt) step(acc, M1_{}, T_{}, true);
+            for (int kt = 0; kt + 2 < nk; ++kt) {
+                const bool copy_now = COPY && (kt % SC_PERIOD) == 0;
+                if (copy_now) copy_issue();
+                step(acc, M1_{}, T_{}, true);
+                if (copy_now) copy_store();
+            }
             if (has_next) {
                 set_a_sources(nxt);
                 set_b_sources(nxt, nxt_n0);
@@ -477,6 +565,10 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
         cur = nxt;
         cur_n0 = nxt_n0;
         job = next_job;
+    }
+    if (COPY) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        copy_rest();
     }
 }
 

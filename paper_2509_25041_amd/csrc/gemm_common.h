@@ -28,6 +28,12 @@ struct GemmArgs {
     int32_t *share_state;
     int64_t share_rows;     // rows of the whole output buffer
     int share_row_vec;      // 16-byte vectors per output row
+    // Row scatter carried along by the launch (null: none): xp[pos[t*k+j]] = x[t], rows of sc_row_bytes
+    // bytes (a multiple of 1024).  Independent of the GEMM's own operands and outputs.
+    const void *sc_x;
+    void *sc_xp;
+    const int32_t *sc_pos;
+    int sc_T, sc_k, sc_row_bytes;
 };
 constexpr int SHARE_STATE_INTS = 8;
 

@@ -66,6 +66,20 @@ int launch_scatter_rows(const void *x, int T, int k, int d, grace_dtype dt, cons
 
 using namespace grace;
 
+extern "C" int grace_permute_rows(const void *x, const int32_t *perm_pos, int32_t T, int32_t k, int32_t d, grace_dtype dt,
+                                  void *xp, void *stream) {
+    if (T < 0 || k < 1 || d < 1) return fail(GRACE_EINVAL, "permute_rows: T=%d, k=%d, d=%d invalid", T, k, d);
+    if (dt != GRACE_F32 && dt != GRACE_BF16) return fail(GRACE_EINVAL, "permute_rows: unknown dtype %d", (int)dt);
+    if ((int64_t)T * k > INT32_MAX) return fail(GRACE_ESHAPE, "permute_rows: T*k exceeds 2^31-1");
+    const size_t el = dt == GRACE_F32 ? 4 : 2;
+    if (((size_t)d * el) % 16 != 0)
+        return fail(GRACE_ESHAPE, "permute_rows: row of %zu bytes is not a multiple of 16", (size_t)d * el);
+    if (T == 0) return GRACE_OK;
+    if (!x || !perm_pos || !xp) return fail(GRACE_EINVAL, "permute_rows: null device pointer");
+    if ((((uintptr_t)x) | ((uintptr_t)xp)) & 15) return fail(GRACE_EINVAL, "permute_rows: x and xp must be 16-byte aligned");
+    return launch_scatter_rows(x, T, k, d, dt, perm_pos, xp, (hipStream_t)stream);
+}
+
 extern "C" int grace_permute(const grace_table *table, const int32_t *topk_inst, int32_t T, int32_t k, const void *x,
                              int32_t d, grace_dtype dt, int32_t *perm_pos, int32_t *perm_src, int32_t *inst_off,
                              int32_t *rank_off, int32_t *node_off, void *xp, void *ws, void *stream) {

@@ -65,6 +65,11 @@ class GraceMoELayer:
         # routing and permutation as one call (fewer launches than grace_route + grace_permute);
         # False: the two separate calls
         self.single_call_dispatch = True
+        # with shared experts: the dispatch call builds only the index arrays and the row scatter rides
+        # on the shared experts' gate+up projection (grace_shared_ffn_up_scatter), which then runs
+        # ahead of the expert FFN; False: the scatter is part of the dispatch call
+        self.fuse_scatter = self.n_shared > 0
+        self.ws_shared = None
         self._key = None
         self._calls: List[Tuple[str, object, tuple]] = []
 
@@ -85,17 +90,28 @@ class GraceMoELayer:
         wg, wu, wd = self.w
         S = wg.shape[0]
         ws = p(self.ws)
+        fuse = self.fuse_scatter and self.shared is not None
+        xr, xpr = (None, None) if fuse else (p(x), p(self.xp))     # rows moved by the dispatch call, or not
         if self.single_call_dispatch:
             calls = [("route_permute", lib.grace_route_permute,
                       (h, lr, self.policy, p(logits), T, self.table.E, k, self.renorm, p(rr_in), p(rr_out), p(te), p(tw),
-                       p(ti), p(cnt), p(x), d, dt, p(pos), p(src), p(ioff), p(roff), p(noff), p(self.xp), ws, st))]
+                       p(ti), p(cnt), xr, d, dt, p(pos), p(src), p(ioff), p(roff), p(noff), xpr, ws, st))]
         else:
             calls = [
                 ("route", lib.grace_route, (h, lr, self.policy, p(logits), T, self.table.E, k, self.renorm, p(rr_in),
                                             p(rr_out), p(te), p(tw), p(ti), p(cnt), ws, st)),
-                ("permute", lib.grace_permute, (h, p(ti), T, k, p(x), d, dt, p(pos), p(src), p(ioff), p(roff), p(noff),
-                                                p(self.xp), ws, st)),
+                ("permute", lib.grace_permute, (h, p(ti), T, k, xr, d, dt, p(pos), p(src), p(ioff), p(roff), p(noff),
+                                                xpr, ws, st)),
             ]
+        if fuse:
+            # the shared gate+up projection first: its hidden activation needs a workspace of its own,
+            # because the expert FFN's hidden activation is written before the shared down projection runs
+            sg, su, sd = self.shared
+            if self.ws_shared is None:
+                self.ws_shared = torch.empty(grace_workspace_bytes(T, 1, 1, 1, d, f, self.n_shared, dt), dtype=torch.uint8,
+                                             device=self.xp.device)
+            calls.append(("shared_up", lib.grace_shared_ffn_up_scatter, (p(x), T, d, f, self.n_shared, dt, p(sg), p(su),
+                                                                        p(self.ws_shared), p(pos), k, p(self.xp), st)))
         calls += [
             ("ffn_up", lib.grace_expert_ffn_up_share, (h, lr, p(self.xp), p(ioff), T, k, d, f, dt, p(wg) if S else None,
                                                        p(wu) if S else None, p(self.y_state), ws, st)),
@@ -104,9 +120,10 @@ class GraceMoELayer:
         ]
         if self.shared is not None:
             sg, su, sd = self.shared
-            calls.append(("shared_up", lib.grace_shared_ffn_up, (p(x), T, d, f, self.n_shared, dt, p(sg), p(su), ws, st)))
+            if not fuse:
+                calls.append(("shared_up", lib.grace_shared_ffn_up, (p(x), T, d, f, self.n_shared, dt, p(sg), p(su), ws, st)))
             calls.append(("shared_down", lib.grace_shared_ffn_down, (T, d, f, self.n_shared, dt, p(sd), p(self.y_shared),
-                                                                     ws, st)))
+                                                                     p(self.ws_shared) if fuse else ws, st)))
         calls.append(("combine", lib.grace_combine, (p(self.y), p(pos), p(tw), T, k, d, dt, p(self.y_shared),
                                                      p(self.out), st)))
         return calls

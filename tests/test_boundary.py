@@ -76,6 +76,9 @@ def test_null_and_range_checks_without_device():
     assert lib.grace_combine(None, None, None, 0, 1, 8, 1, None, None, None) == 0                # nothing to do
     assert lib.grace_mfma_sustained(1, 1, None, None) == -1
     assert lib.grace_table_set_fold_limits(None, -1, -1) == -1
+    assert lib.grace_permute_rows(None, None, 1, 1, 8, 1, None, None) == -1
+    assert lib.grace_shared_ffn_up_scatter(None, 1, 8, 8, 1, 1, None, None, None, None, 0, None, None) == -1
+    assert lib.grace_permute_rows(None, None, 0, 1, 8, 1, None, None) == 0
     assert lib.grace_route_permute_static(None, 0, 0, None, 1, 1, 1, 1, None, None, None, None, None, None, None, 8, 1, None,
                                           None, None, None, None, None, None) == -1
     assert lib.grace_expert_ffn_up_share(None, 0, None, None, 1, 1, 8, 8, 1, None, None, None, None, None) == -1

@@ -492,6 +492,51 @@ def test_more_than_64_local_slots_element_by_element():
     assert rel_err(oracle.widen(host(y))[lo:hi], want[lo:hi]) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("T,d,f,n_shared,k,dtype", [
+    (3000, 512, 384, 2, 6, "bf16"),     # 1 KB rows, 12 row tiles x 6 column tiles: every workgroup has K steps to copy in
+    (300, 4096, 128, 1, 3, "bf16"),     # 8 KB rows, 2 tiles for 256 workgroups: nearly all rows moved after the tile loop
+    (5000, 1024, 1024, 1, 1, "bf16"),   # k = 1
+    (700, 2048, 256, 3, 64, "bf16"),    # k = 64: the largest top-k
+    (333, 136, 200, 1, 2, "bf16"),      # 272-byte rows: the scatter runs as a launch of its own
+    (150, 128, 76, 3, 3, "f32"),        # fp32: likewise
+])
+def test_shared_up_with_row_scatter_equals_the_two_calls(T, d, f, n_shared, k, dtype):
+    """grace_shared_ffn_up_scatter (the shared gate+up projection carrying the row scatter) against
+    grace_shared_ffn_up + grace_permute_rows, bit for bit, and the rows against the oracle's gather;
+    positions outside the buffer (-1: expert outside the table) are skipped."""
+    rng = np.random.default_rng(T + d)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    x = torch.from_numpy(rng.standard_normal((T, d)).astype(np.float32)).cuda().to(tdt)
+    wg = torch.from_numpy((0.05 * rng.standard_normal((n_shared, f, d))).astype(np.float32)).cuda().to(tdt)
+    wu = torch.from_numpy((0.05 * rng.standard_normal((n_shared, f, d))).astype(np.float32)).cuda().to(tdt)
+    perm = rng.permutation(T * k).astype(np.int32)              # any bijection is a valid dispatch order here
+    pos_h = perm.copy()
+    dropped = rng.choice(T * k, size=max(1, T * k // 50), replace=False)
+    pos_h[dropped] = -1
+    pos = torch.from_numpy(pos_h).cuda()
+    nbytes = grace.grace_workspace_bytes(T, 1, 1, 1, d, f, n_shared, grace.GRACE_F32 if dtype == "f32" else grace.GRACE_BF16)
+    ws_a = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    ws_b = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    xp_a = torch.full((T * k, d), 7.0, dtype=tdt, device="cuda")
+    xp_b = torch.full((T * k, d), 7.0, dtype=tdt, device="cuda")
+    grace.grace_shared_ffn_up_scatter(x, wg, wu, ws_a, pos, k, xp_a)
+    lib = grace.load_library()
+    import ctypes as C
+    from paper_2509_25041_amd.binding import _check, _dp, _dtype_code, _stream
+    _check(lib.grace_shared_ffn_up(_dp(x), T, d, f, n_shared, _dtype_code(x), _dp(wg), _dp(wu), _dp(ws_b), _stream()))
+    grace.grace_permute_rows(x, pos, k, xp_b)
+    torch.cuda.synchronize()
+    assert torch.equal(ws_a, ws_b)                                   # the hidden activation, bit for bit
+    assert torch.equal(xp_a.view(torch.uint8), xp_b.view(torch.uint8))
+    # rows against the definition: xp[p] = x[a // k] where perm_pos[a] = p; dropped positions keep their old contents
+    got, xh = host(xp_a), host(x)
+    keep = pos_h >= 0
+    np.testing.assert_array_equal(got[pos_h[keep]], xh[np.nonzero(keep)[0] // k])
+    untouched = np.setdiff1d(np.arange(T * k), pos_h[keep])
+    assert len(untouched) == len(dropped)
+    np.testing.assert_array_equal(got[untouched], host(torch.full((len(untouched), d), 7.0, dtype=tdt)))
+
+
 def test_layer_object_rank_share_matches_oracle():
     cfg = SMALL["bf16_small"]
     wl = make_workload(cfg)
