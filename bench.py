@@ -256,6 +256,32 @@ def run_workload(name: str, steps: int, warmup: int, rotate: int = 0, mfma_probe
         with open(tpath) as fh:
             traffic = json.load(fh).get("per_stage_hbm_bytes_per_launch", {}).get(dominant)
 
+    # the shared gate+up projection carries the row scatter: also time the projection by itself (outside the
+    # timed region), so that the line shows what the scatter costs it
+    carried = None
+    if fused_scatter and dominant == "shared_up":
+        import ctypes as C
+        lib = grace.load_library()
+        sg, su, _ = shd
+        pp = lambda t: C.c_void_p(t.data_ptr())
+        args = (pp(x), T, d, f, cfg.n_shared, layer.dt, pp(sg), pp(su), pp(layer.ws_shared),
+                C.c_void_p(torch.cuda.current_stream().cuda_stream))
+        evs = []
+        for i in range(steps + 3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            rc = lib.grace_shared_ffn_up(*args)
+            e1.record()
+            assert rc == 0
+            if i >= 3:
+                evs.append((e0, e1))
+        torch.cuda.synchronize()
+        alone_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
+        sc_bytes = float(T * d * el + T * k * d * el)
+        carried = {"what": "row scatter of the dispatch permutation (grace_permute_rows), moved by the same launch",
+                   "bytes": sc_bytes, "projection_alone_ms": alone_ms,
+                   "projection_alone_frac": work[dominant][1] / (alone_ms * 1e-3) / 1e12 / peak_mm,
+                   "cost_of_carrying_ms": dom_ms - alone_ms}
     ach, peak, unit = achieved(dominant, dom_ms)
     stages_achieved = {}
     for s in stage_ms:
@@ -280,7 +306,7 @@ def run_workload(name: str, steps: int, warmup: int, rotate: int = 0, mfma_probe
         "roofline": {"kernel": KERNEL_OF_STAGE[dominant] if cfg.dtype == "bf16" else f"{dominant} (fp32 FMA path)",
                      "stage": dominant, "bound": work[dominant][0], "achieved": ach, "peak": peak, "unit": unit,
                      "frac": ach / peak, "traffic": traffic, "avg_launch_ms": dom_ms,
-                     "algorithmic_per_launch": work[dominant][1]},
+                     "algorithmic_per_launch": work[dominant][1], "carries": carried},
         "stages_ms": stage_ms,
         "stages_achieved": stages_achieved,
         "graph_replay_ms_per_step": graph_ms,
