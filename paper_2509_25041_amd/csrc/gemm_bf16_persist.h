@@ -52,6 +52,7 @@ namespace pers {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef const __attribute__((address_space(1))) void global_void_t;
 
@@ -67,6 +68,8 @@ constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BROWS * ROW_BYTES;
 constexpr int B_BASE = NBUF_A * A_BYTES;       // weight buffers follow the activation buffers
 constexpr int LDS_BYTES = NBUF_A * A_BYTES + NBUF_B * B_BYTES;
 constexpr int MAX_SEG_PER_LANE = 4, MAX_SEGMENTS = 64 * MAX_SEG_PER_LANE;
+// Which MFMA the K loop issues: v_mfma_f32_16x16x32_bf16 (true) or v_mfma_f32_32x32x16_bf16.
+constexpr bool M16 = true;
 
 template <bool FUSED_UP>
 struct Shape {
@@ -323,6 +326,31 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     for (int ks = 0; ks < KS; ++ks) pc[ks] = ((ks * 2 + fhalf) ^ fkey) * 16;
 
     bf16x8_t fa[2][4], fb[2][2];
+    // The same for v_mfma_f32_16x16x32_bf16: a fragment is 16 rows x 32 K, row = base + (lane & 15), chunk
+    // 4 * g + (lane >> 4) of the step's K group g (two per step); per wavefront and group 4 weight fragments
+    // (FUSED_UP: two of the gate rows, two of the up rows) and 8 activation fragments.
+    const int frow16 = lane & 15, fkey16 = swizzle_key(frow16);
+    const int a_base16 = (wm * 128 + frow16) * ROW_BYTES;
+    const int b_base16 = ((FUSED_UP ? wn * 32 : wn * 64) + frow16) * ROW_BYTES;
+    int pc16[2];
+#pragma unroll
+    for (int gk = 0; gk < 2; ++gk) pc16[gk] = ((gk * 4 + (lane >> 4)) ^ fkey16) * 16;
+    bf16x8_t ga[2][8], gb[2][4];
+    // fragment r of a K group: r < 4 weight rows, else activation rows
+    auto fetch16_one = [&](int buf, const char *sa, const char *sb, int gk, int r) {
+        if (r < 4) {
+            const int rows = FUSED_UP ? (r >> 1) * 128 + (r & 1) * 16 : r * 16;
+            gb[buf][r] = *(const bf16x8_t *)(sb + b_base16 + rows * ROW_BYTES + pc16[gk]);
+        } else {
+            ga[buf][r - 4] = *(const bf16x8_t *)(sa + a_base16 + (r - 4) * 16 * ROW_BYTES + pc16[gk]);
+        }
+    };
+    // what a K group needs on entry: its activation fragments and weight fragments 0, 1
+    auto fetch16 = [&](int buf, const char *sa, const char *sb, int gk) {
+#pragma unroll
+        for (int r = 0; r < 12; ++r)
+            if (r < 2 || r >= 4) fetch16_one(buf, sa, sb, gk, r);
+    };
     // fragment r of a 16-wide K group: r < 2 weight rows, else activation rows
     auto fetch_one = [&](int buf, const char *sa, const char *sb, int ks, int r) {
         if (r < 2) fb[buf][r] = *(const bf16x8_t *)(sb + b_off[r] + pc[ks]);
@@ -428,6 +456,111 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
             __builtin_amdgcn_sched_barrier(0);
         }
     };
+    // The step with v_mfma_f32_16x16x32_bf16: two K groups of 32 MFMAs each, in two passes: the eight
+    // activation fragments with weight fragments 0 and 1, then with 2 and 3.  Registers: the activation
+    // fragments live through the group; weight fragments 2 and 3 of a group are read during its first
+    // pass, and during the second pass the next group's weight fragments 0, 1 (into the registers pass one
+    // has freed) and its activation fragment i right after the current fragment i has had its last MFMA.
+    // The one wait + barrier of the step stands between its two groups, so the second group's weight
+    // fragments 2, 3 are read ahead of it as well (every read of the step's buffers precedes the barrier);
+    // the second group's second pass reads the next step's first fragments from the next buffers.
+    // RD_POS: fragment read r (r < 4 weight, else activation r - 4) is issued after the group's MFMA number ..
+    constexpr int RD_CUR_POS[2] = {0, 1};                                      // this group's weight fragments 2, 3
+    constexpr int RD_NXT[10] = {0, 1, 4, 5, 6, 7, 8, 9, 10, 11};               // next group: weights 0, 1, activations 0..7
+    constexpr int RD_NXT_POS[10] = {16, 17, 18, 20, 22, 24, 26, 28, 30, 31};
+    constexpr int RD_NXT23_POS[2] = {19, 21};                                  // next group's weights 2, 3 (before a barrier)
+    constexpr int LD_POS[4] = {3, 7, 11, 15};                                  // direct-to-LDS loads of the step
+    auto mfma_group16 = [&](f32x4_t (&acc)[8][4], int cur) {
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass)
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int jl = 0; jl < 2; ++jl) {
+                    const int j = pass * 2 + jl;
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gb[cur][j], ga[cur][i], acc[i][j], 0, 0, 0);
+                }
+    };
+    // reads and loads of one group in program order = issue order; `own23`: this group's weight fragments
+    // 2, 3 are still to be read (not so after a barrier); `next`: read the next group's fragments from
+    // (na, nb, ngk) into buffer nbuf, `next23` including its weight fragments 2, 3
+    auto group_reads16 = [&](int cur, const char *ca, const char *cb, int cgk, bool own23, bool next, bool next23, int nbuf,
+                             const char *na, const char *nb, int ngk, auto issue_one, bool loads) {
+#pragma unroll
+        for (int m = 0; m < 32; ++m) {
+            if (own23) {
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+                    if (RD_CUR_POS[q] == m) fetch16_one(cur, ca, cb, cgk, 2 + q);
+            }
+            if (next) {
+#pragma unroll
+                for (int q = 0; q < 10; ++q)
+                    if (RD_NXT_POS[q] == m) fetch16_one(nbuf, na, nb, ngk, RD_NXT[q]);
+                if (next23) {
+#pragma unroll
+                    for (int q = 0; q < 2; ++q)
+                        if (RD_NXT23_POS[q] == m) fetch16_one(nbuf, na, nb, ngk, 2 + q);
+                }
+            }
+            if (loads) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (LD_POS[q] == m) issue_one(q);
+            }
+        }
+    };
+    auto group_sched16 = [&](bool own23, bool next, bool next23, bool loads) {
+#pragma unroll
+        for (int m = 0; m < 32; ++m) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+            int reads = 0;
+            if (own23)
+                for (int q = 0; q < 2; ++q) reads += RD_CUR_POS[q] == m;
+            if (next) {
+                for (int q = 0; q < 10; ++q) reads += RD_NXT_POS[q] == m;
+                if (next23)
+                    for (int q = 0; q < 2; ++q) reads += RD_NXT23_POS[q] == m;
+            }
+            if (reads == 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS reads
+            if (reads == 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            if (loads) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (LD_POS[q] == m) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);   // 1 VMEM
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto step16 = [&](f32x4_t (&acc)[8][4], auto load_mode, auto cross, bool flag) {
+        constexpr int LOAD_MODE = decltype(load_mode)::value;
+        constexpr bool CROSS = decltype(cross)::value, STEADY = LOAD_MODE == 1;
+        const char *sa = smem + a_con * A_BYTES, *sb = smem + B_BASE + b_con * B_BYTES;
+        a_con ^= 1;
+        b_con = (b_con + 1 == NBUF_B) ? 0 : b_con + 1;
+        const char *sa_next = smem + a_con * A_BYTES, *sb_next = smem + B_BASE + b_con * B_BYTES;
+        // ---- first K group: weight loads of step g + 2; reads of this step's second group ----
+        if (!STEADY && flag) {   // tile boundary: the conditional loads sit in a basic block of their own
+#pragma unroll
+            for (int q = 0; q < 4; ++q) issue_b_one(q);
+        }
+        group_reads16(0, sa, sb, 0, true, true, true, 1, sa, sb, 1, issue_b_one, STEADY);
+        mfma_group16(acc, 0);
+        group_sched16(true, true, true, STEADY);
+        // ---- second K group ----
+        if (STEADY || flag) {
+            advance_b();
+            asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        }
+        asm volatile("s_barrier" ::: "memory");
+        if (!STEADY && flag) issue_a();
+        group_reads16(1, sa, sb, 1, false, CROSS, false, 0, sa_next, sb_next, 0, issue_a_one, STEADY);
+        if (STEADY) advance_a();
+        mfma_group16(acc, 1);
+        group_sched16(false, CROSS, false, STEADY);
+    };
     // the same step for a wavefront with no valid rows in this tile: synchronise and load only
     auto idle_step = [&](bool loads_on) {
         a_con ^= 1;
@@ -503,6 +636,52 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
         }
     };
 
+    // The same for the 16x16 blocks of v_mfma_f32_16x16x32_bf16: acc[i][j] holds element v of lane l at
+    // (n = 4 * (l / 16) + v, m = l % 16) of block (rows 16 i .., columns 16 j ..); FUSED_UP: j < 2 gate, j >= 2
+    // the up projection of the same columns.  Two blocks i make one staged 32-row sub-tile.
+    auto epilogue16 = [&](f32x4_t (&acc)[8][4], const Tile &t, int n0, int n_valid) {
+        uint16_t *out = (uint16_t *)g.out;
+        constexpr int ROWS_PER_IT = 64 / CH;
+        const int el = opaque_lane(), er = el & 15, eq = el >> 4;   // not kept across the K loop
+        const int rr = el / CH, cc = el % CH;
+        const int ncol = n0 + wn * BNW + cc * 8;
+        char *stg = smem + B_BASE + b_iss * B_BYTES;  // the buffer read in the tile's last step
+#pragma unroll
+        for (int i32 = 0; i32 < 4; ++i32) {
+            if (i32 >= n_valid) break;
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                const int i = i32 * 2 + sub, row = sub * 16 + er;
+                const int wkey = (row >> KSH) & (CH - 1);
+#pragma unroll
+                for (int jn = 0; jn < (FUSED_UP ? 2 : 4); ++jn) {
+                    float h[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        if (FUSED_UP) {
+                            const float gt = acc[i][jn][r], up = acc[i][jn + 2][r];
+                            h[r] = gt * __frcp_rn(1.0f + __expf(-gt)) * up;
+                        } else {
+                            h[r] = acc[i][jn][r];
+                        }
+                    }
+                    const uint2 pk = make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
+                    // columns 16 jn + 4 eq .. +3: chunk 2 jn + eq / 2, its low or high 8 bytes
+                    *(uint2 *)(stg + stg_off(row * ROWB + (((jn * 2 + (eq >> 1)) ^ wkey) * 16) + (eq & 1) * 8)) = pk;
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wavefront's own writes, read back below
+#pragma unroll
+            for (int it = 0; it < 32 / ROWS_PER_IT; ++it) {
+                const int ml = it * ROWS_PER_IT + rr;
+                const int row = t.m0 + wm * 128 + i32 * 32 + ml;
+                const int key = (ml >> KSH) & (CH - 1);
+                const uint4 v = *(const uint4 *)(stg + stg_off(ml * ROWB + ((cc ^ key) * 16)));
+                if (row < t.m_end && ncol < g.N) *(uint4 *)(out + (int64_t)row * g.ldo + ncol) = v;
+            }
+        }
+    };
+
     // ---- tile loop ----------------------------------------------------------------------------------
     // Per tile of nk steps: steps 0 .. nk-3 load this tile's steps 2 .. nk-1; steps nk-2 and nk-1
     // load steps 0 and 1 of the next tile, if there is one.
@@ -529,7 +708,30 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
         }
         // 32-row sub-tiles of this wavefront that hold at least one valid row (scalar)
         const int n_valid = max(0, min(4, (cur.m_end - (cur.m0 + wm * 128) + 31) / 32));
-        if (n_valid > 0) {
+        if (n_valid > 0 && M16) {
+            f32x4_t acc[8][4];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
+            fetch16(0, smem + a_con * A_BYTES, smem + B_BASE + b_con * B_BYTES, 0);
+            for (int kt = 0; kt + 2 < nk; ++kt) {
+                const bool copy_now = COPY && (kt % SC_PERIOD) == 0;
+                if (copy_now) copy_issue();
+                step16(acc, M1_{}, T_{}, true);
+                if (copy_now) copy_store();
+            }
+            // the last two steps load the first two of the next tile; without one they load this tile's
+            // again (valid addresses, nobody reads them), so that every step is the same straight code
+            set_a_sources(nxt);
+            set_b_sources(nxt, nxt_n0);
+            step16(acc, M1_{}, T_{}, true);
+            step16(acc, M1_{}, F_{}, true);
+            epilogue16(acc, cur, cur_n0, n_valid);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // staging reads done before the buffer is refilled
+        } else if (n_valid > 0) {
             f32x16_t acc[4][2];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -554,22 +756,20 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // staging reads done before the buffer is refilled
         } else {
             for (int kt = 0; kt + 2 < nk; ++kt) idle_step(true);
-            if (has_next) {
+            if (has_next || M16) {
                 set_a_sources(nxt);
                 set_b_sources(nxt, nxt_n0);
             }
-            idle_step(has_next);
-            idle_step(has_next);
+            idle_step(has_next || M16);
+            idle_step(has_next || M16);
         }
         if (!has_next) break;
         cur = nxt;
         cur_n0 = nxt_n0;
         job = next_job;
     }
-    if (COPY) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        copy_rest();
-    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no load may still be on its way to LDS when the workgroup ends
+    if (COPY) copy_rest();
 }
 
 // Workgroups to launch on a device with `n_cu` compute units: one per compute unit, a multiple of 8.
