@@ -341,8 +341,8 @@ int grace_combine(const void *y, const int32_t *perm_pos, const float *topk_weig
 
 /* ---- diagnostics ---------------------------------------------------------------
  * Measures the bf16 MFMA rate the current device sustains with the grouped GEMM's
- * inner instruction mix and no global traffic (8 wavefronts per CU, one barrier
- * per 32 MFMAs): constant or pseudo-random operands (a power-limited part runs
+ * inner instruction mix (v_mfma_f32_16x16x32_bf16, 12 fragment reads per 32 of them)
+ * and no global traffic (8 wavefronts per CU, one barrier per 64 MFMAs): constant or pseudo-random operands (a power-limited part runs
  * slower the more operand bits toggle), fragments held in registers or re-read
  * from LDS.  NOT for the hot path and the one exception to the conventions
  * above: it allocates and frees a small device buffer (hipMalloc / hipFree),

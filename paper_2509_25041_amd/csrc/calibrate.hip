@@ -3,15 +3,16 @@
 // The MFMA rate of a power-limited part depends on how many operand bits
 // toggle, so the nominal peak is not what a GEMM on real data can reach.  This
 // kernel issues the grouped GEMM's inner instruction mix with no global
-// traffic: per group 8 x v_mfma_f32_32x32x16_bf16 and (optionally) 6 16-byte
-// fragment reads from LDS for the next group, 8 wavefronts per CU, one barrier
-// per 32 MFMAs, with constant or pseudo-random bf16 operands.
+// traffic: per K group 32 x v_mfma_f32_16x16x32_bf16 (eight activation
+// fragments x four weight fragments, in the GEMM's two passes) and (optionally)
+// 12 16-byte fragment reads from LDS for the next group, 8 wavefronts per CU,
+// one barrier per 64 MFMAs, with constant or pseudo-random bf16 operands.
 #include "common.h"
 
 namespace grace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 cal_bf16x8_t;
-typedef __attribute__((ext_vector_type(16))) float cal_f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float cal_f32x4_t;
 
 template <bool LDS_FED>
 __global__ __launch_bounds__(512) void mfma_sustained_kernel(float *out, int iters, int random_operands) {
@@ -26,36 +27,42 @@ __global__ __launch_bounds__(512) void mfma_sustained_kernel(float *out, int ite
         ((unsigned *)smem)[i] = random_operands ? (lo | (hi << 16)) : 0x3C003C00u;
     }
     __syncthreads();
-    cal_f32x16_t acc[8];
+    cal_f32x4_t acc[8][4];
     for (int i = 0; i < 8; ++i)
-        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
-    // the grouped GEMM's fragment addressing: 128-byte rows, chunk ^ ((row >> 1) & 7)
-    const int row = lane & 31, half = lane >> 5;
-    const int base = (wave & 3) * 8192 + row * 128 + ((half ^ ((row >> 1) & 7)) * 16);
-    cal_bf16x8_t f[2][6];
+        for (int j = 0; j < 4; ++j)
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
+    // the grouped GEMM's fragment addressing: 128-byte rows, 16 rows per fragment, chunk ^ ((row >> 1) & 7)
+    const int row = lane & 15, quarter = lane >> 4;
+    const int base = (wave & 3) * 8192 + row * 128;
+    int pc[2];
+    for (int gk = 0; gk < 2; ++gk) pc[gk] = ((gk * 4 + quarter) ^ ((row >> 1) & 7)) * 16;
+    cal_bf16x8_t f[2][12];  // per K group: fragments 0..3 weights, 4..11 activations
     for (int b = 0; b < 2; ++b)
-        for (int r = 0; r < 6; ++r) f[b][r] = *(const cal_bf16x8_t *)(smem + base + ((r * 4096 + b * 32) & 0x7FFF));
+        for (int r = 0; r < 12; ++r) f[b][r] = *(const cal_bf16x8_t *)(smem + ((base + r * 2048 + pc[b]) & 0xFFFF));
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int grp = 0; grp < 4; ++grp) {
-            const int cur = grp & 1, nxt = cur ^ 1;
+        for (int grp = 0; grp < 2; ++grp) {
+            const int cur = grp, nxt = grp ^ 1;
             if (LDS_FED) {
 #pragma unroll
-                for (int r = 0; r < 6; ++r)
-                    f[nxt][r] = *(const cal_bf16x8_t *)(smem + base + ((r * 4096 + grp * 32 + (it & 1) * 64) & 0x7FFF));
+                for (int r = 0; r < 12; ++r)
+                    f[nxt][r] = *(const cal_bf16x8_t *)(smem + ((base + r * 2048 + pc[nxt] + (it & 1) * 32768) & 0xFFFF));
             }
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int pass = 0; pass < 2; ++pass)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i * 2 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[cur][2 + i], f[cur][j], acc[i * 2 + j], 0, 0, 0);
+                for (int i = 0; i < 8; ++i)
+#pragma unroll
+                    for (int jl = 0; jl < 2; ++jl) {
+                        const int j = pass * 2 + jl;
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[cur][j], f[cur][4 + i], acc[i][j], 0, 0, 0);
+                    }
             if (LDS_FED) {
 #pragma unroll
-                for (int r = 0; r < 6; ++r) {
+                for (int m = 0; m < 32; ++m) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    if (m >= 16 && m < 28) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 }
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -64,7 +71,8 @@ __global__ __launch_bounds__(512) void mfma_sustained_kernel(float *out, int ite
     }
     float s = 0;
     for (int i = 0; i < 8; ++i)
-        for (int v = 0; v < 16; ++v) s += acc[i][v];
+        for (int j = 0; j < 4; ++j)
+            for (int v = 0; v < 4; ++v) s += acc[i][j][v];
     out[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
 }
 
@@ -102,7 +110,7 @@ extern "C" int grace_mfma_sustained(int32_t random_operands, int32_t lds_fed, do
     if (e1) (void)hipEventDestroy(e1);
     (void)hipFree(out);
     if (he != hipSuccess) return fail(GRACE_EHIP, "mfma_sustained: %s", hipGetErrorString(he));
-    const double flops = (double)blocks * 8 * iters * 32 * 32768.0;
+    const double flops = (double)blocks * 8 * iters * 64 * 16384.0;   // 64 MFMAs of 16 x 16 x 32 x 2 FLOP per iteration
     *tflops_out = flops / (best * 1e-3) / 1e12;
     return GRACE_OK;
 }

@@ -2,7 +2,10 @@
 //
 // One workgroup per compute unit walks a list of output tiles.  Tile = 256
 // activation rows x 256 weight rows, K in steps of 64, 8 wavefronts (2 along M
-// x 4 along N, 128 x 64 outputs each, 32x32x16 MFMA).  Both operands are
+// x 4 along N, 128 x 64 outputs each, v_mfma_f32_16x16x32_bf16: on this part,
+// whose MFMA rate is set by the power limit, it sustains about a tenth more
+// than the 32x32x16 form at the same operand traffic, having a quarter of the
+// accumulator values per instruction for half the arithmetic).  Both operands are
 // K-contiguous in HBM and are copied HBM -> LDS with direct-to-LDS 16-byte
 // loads (no staging registers); the 16-byte chunk c of tile row r is kept at
 // chunk position c ^ ((r >> 1) & 7) (conflict-free fragment reads), applied on
@@ -11,16 +14,18 @@
 //
 // All 160 KB of LDS hold operand buffers: two for the activation tile and
 // three for the weight tile (32 KB each).  The K loop is flattened over the
-// workgroup's tiles.  Step g issues the weight loads of step g + 2 spread over
-// its first three 16-wide K groups (their buffer was read in step g - 1) and,
-// after the one barrier of the step, once every wavefront has read the buffers
-// of step g, the activation loads of step g + 2; whether step g + 2 is in the
-// same tile or the next one.  A batch of loads needs longer than one step to
-// land, which a plain double buffer cannot hide; with this split the weight
-// batch has more than a step and a half, the activation batch is half as large,
-// and the loads are spread over the step instead of issued in one burst.  The
-// pipeline never drains between tiles: the first steps of the next tile are in
-// flight while the current tile's accumulators are converted and written out.
+// workgroup's tiles.  Step g issues the weight loads of step g + 2 during its
+// first 32-wide K group (their buffer was read in step g - 1) and, after the one
+// barrier of the step, once every wavefront has read the buffers of step g, the
+// activation loads of step g + 2 during its second K group; whether step g + 2
+// is in the same tile or the next one.  A batch of loads needs longer than one
+// step to land, which a plain double buffer cannot hide; with this split the
+// weight batch has more than a step and a half, the activation batch is half as
+// large, and the loads are spread over the step instead of issued in one burst.
+// The pipeline never drains between tiles: the first steps of the next tile are
+// in flight while the current tile's accumulators are converted and written out
+// (a workgroup's last tile loads its own first steps again instead: valid
+// addresses that nobody reads, so that every step is the same straight code).
 // The epilogue stages through the weight buffer that was read last (each
 // wavefront uses exactly the bytes its own next weight loads will overwrite),
 // so it needs no workgroup barrier.
@@ -51,13 +56,12 @@ namespace grace {
 namespace pers {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef const __attribute__((address_space(1))) void global_void_t;
 
 constexpr int BM = 256, BROWS = 256, THREADS = 512, N_XCD = 8;
-constexpr int BK = 64, KS = BK / 16;
+constexpr int BK = 64;
 constexpr int NBUF_A = 2, NBUF_B = 3;          // LDS buffers per operand
 constexpr int MIN_K_STEPS = 2;
 constexpr int ROW_BYTES = BK * 2;              // one tile row in LDS
@@ -68,8 +72,6 @@ constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BROWS * ROW_BYTES;
 constexpr int B_BASE = NBUF_A * A_BYTES;       // weight buffers follow the activation buffers
 constexpr int LDS_BYTES = NBUF_A * A_BYTES + NBUF_B * B_BYTES;
 constexpr int MAX_SEG_PER_LANE = 4, MAX_SEGMENTS = 64 * MAX_SEG_PER_LANE;
-// Which MFMA the K loop issues: v_mfma_f32_16x16x32_bf16 (true) or v_mfma_f32_32x32x16_bf16.
-constexpr bool M16 = true;
 
 template <bool FUSED_UP>
 struct Shape {
@@ -313,164 +315,56 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
         advance_b();
     };
 
-    // fragment addresses: row r = base + (lane & 31), chunk c = 2*ks + (lane >> 5) stored at c ^ key(r)
-    const int frow = lane & 31, fhalf = lane >> 5, fkey = swizzle_key(frow);  // bases are multiples of 32
-    int a_off[4], b_off[2];
+    // fragments of v_mfma_f32_16x16x32_bf16: 16 rows x 32 K, row = base + (lane & 15) (bases are multiples
+    // of 16), chunk 4 * g + (lane >> 4) of the step's K group g (two per step) stored at chunk ^ key(row);
+    // per wavefront and group 4 weight fragments (FUSED_UP: two of the gate rows, two of the up rows)
+    // and 8 activation fragments.
+    const int frow = lane & 15, fkey = swizzle_key(frow);
+    const int a_base = (wm * 128 + frow) * ROW_BYTES;
+    const int b_base = ((FUSED_UP ? wn * 32 : wn * 64) + frow) * ROW_BYTES;
+    int pc[2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) a_off[i] = (wm * 128 + i * 32 + frow) * ROW_BYTES;
-#pragma unroll
-    for (int jj = 0; jj < 2; ++jj)
-        b_off[jj] = ((FUSED_UP ? jj * 128 + wn * 32 : wn * 64 + jj * 32) + frow) * ROW_BYTES;
-    int pc[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) pc[ks] = ((ks * 2 + fhalf) ^ fkey) * 16;
-
-    bf16x8_t fa[2][4], fb[2][2];
-    // The same for v_mfma_f32_16x16x32_bf16: a fragment is 16 rows x 32 K, row = base + (lane & 15), chunk
-    // 4 * g + (lane >> 4) of the step's K group g (two per step); per wavefront and group 4 weight fragments
-    // (FUSED_UP: two of the gate rows, two of the up rows) and 8 activation fragments.
-    const int frow16 = lane & 15, fkey16 = swizzle_key(frow16);
-    const int a_base16 = (wm * 128 + frow16) * ROW_BYTES;
-    const int b_base16 = ((FUSED_UP ? wn * 32 : wn * 64) + frow16) * ROW_BYTES;
-    int pc16[2];
-#pragma unroll
-    for (int gk = 0; gk < 2; ++gk) pc16[gk] = ((gk * 4 + (lane >> 4)) ^ fkey16) * 16;
-    bf16x8_t ga[2][8], gb[2][4];
+    for (int gk = 0; gk < 2; ++gk) pc[gk] = ((gk * 4 + (lane >> 4)) ^ fkey) * 16;
+    bf16x8_t fa[2][8], fb[2][4];
     // fragment r of a K group: r < 4 weight rows, else activation rows
-    auto fetch16_one = [&](int buf, const char *sa, const char *sb, int gk, int r) {
+    auto fetch_one = [&](int buf, const char *sa, const char *sb, int gk, int r) {
         if (r < 4) {
             const int rows = FUSED_UP ? (r >> 1) * 128 + (r & 1) * 16 : r * 16;
-            gb[buf][r] = *(const bf16x8_t *)(sb + b_base16 + rows * ROW_BYTES + pc16[gk]);
+            fb[buf][r] = *(const bf16x8_t *)(sb + b_base + rows * ROW_BYTES + pc[gk]);
         } else {
-            ga[buf][r - 4] = *(const bf16x8_t *)(sa + a_base16 + (r - 4) * 16 * ROW_BYTES + pc16[gk]);
+            fa[buf][r - 4] = *(const bf16x8_t *)(sa + a_base + (r - 4) * 16 * ROW_BYTES + pc[gk]);
         }
     };
     // what a K group needs on entry: its activation fragments and weight fragments 0, 1
-    auto fetch16 = [&](int buf, const char *sa, const char *sb, int gk) {
+    auto fetch_entry = [&](int buf, const char *sa, const char *sb, int gk) {
 #pragma unroll
         for (int r = 0; r < 12; ++r)
-            if (r < 2 || r >= 4) fetch16_one(buf, sa, sb, gk, r);
-    };
-    // fragment r of a 16-wide K group: r < 2 weight rows, else activation rows
-    auto fetch_one = [&](int buf, const char *sa, const char *sb, int ks, int r) {
-        if (r < 2) fb[buf][r] = *(const bf16x8_t *)(sb + b_off[r] + pc[ks]);
-        else fa[buf][r - 2] = *(const bf16x8_t *)(sa + a_off[r - 2] + pc[ks]);
-    };
-    auto fetch = [&](int buf, const char *sa, const char *sb, int ks) {
-#pragma unroll
-        for (int r = 0; r < 6; ++r) fetch_one(buf, sa, sb, ks, r);
+            if (r < 2 || r >= 4) fetch_one(buf, sa, sb, gk, r);
     };
 
     // ---- one K step ---------------------------------------------------------------------------
-    // Weight loads of step g + 2 go out during the first three K groups (two, one, one).  Before the
-    // MFMAs of the last group the workgroup synchronises once: by then every wavefront has read all
-    // of this step's buffers (fragments are fetched one group ahead), so the activation buffer is
-    // handed to the loads of step g + 2, issued right after; and each wavefront has waited for its
-    // own loads of step g + 1, so after the barrier those have landed.  Loads complete in issue
-    // order, so "everything but the newest LOADS loads" covers step g + 1 whenever this step issued
-    // its weight loads; otherwise the wait is for all loads.
-    // LOAD_MODE: 1 issue the loads of step g + 2, 2 only if `flag` (tile boundary without a next
-    // tile).  CROSS: fetch the first fragments of the next step under the last MFMAs (not across a
-    // tile boundary).
+    // Two K groups of 32 MFMAs each, in two passes: the eight activation fragments with weight fragments
+    // 0 and 1, then with 2 and 3.  Registers: the activation fragments live through the group; weight
+    // fragments 2 and 3 of a group are read during its first pass, and during the second pass the next
+    // group's weight fragments 0, 1 (into the registers pass one has freed) and its activation fragment
+    // i right after the current fragment i has had its last MFMA (56 fragment registers plus those in
+    // flight, where holding both groups whole would take 96).
+    // The weight loads of step g + 2 go out during the first group.  Before the second group the
+    // workgroup synchronises once: by then every wavefront has read all of this step's buffers (so the
+    // second group's weight fragments 2, 3 are read ahead of the barrier as well), and the activation
+    // buffer is handed to the loads of step g + 2, issued during the second group; and each wavefront
+    // has waited for its own loads of step g + 1, so after the barrier those have landed.  Loads
+    // complete in issue order, so "everything but the newest LOADS loads" covers step g + 1.  The second
+    // group's second pass reads the next step's first fragments from the next buffers (CROSS; not
+    // across a tile boundary, where the registers are needed for the epilogue).
+    // RD_*_POS: the read is issued after the group's MFMA number ..; LD_POS likewise for the four loads.
     int a_con = 0, b_con = 0;  // buffers the current step reads
-    auto step = [&](f32x16_t (&acc)[4][2], auto load_mode, auto cross, bool flag) {
-        constexpr int LOAD_MODE = decltype(load_mode)::value;
-        constexpr bool CROSS = decltype(cross)::value, STEADY = LOAD_MODE == 1;
-        const char *sa = smem + a_con * A_BYTES, *sb = smem + B_BASE + b_con * B_BYTES;
-        a_con ^= 1;
-        b_con = (b_con + 1 == NBUF_B) ? 0 : b_con + 1;
-        const char *sa_next = smem + a_con * A_BYTES, *sb_next = smem + B_BASE + b_con * B_BYTES;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const int cur = ks & 1, nxt = cur ^ 1;  // KS is even: parity restarts every step
-            const bool last = ks == KS - 1;
-            // program order = issue order wanted: direct loads and fragment reads both touch LDS, so
-            // the compiler keeps them in this order
-            if (!last) {
-                const int first_load = ks == 0 ? 0 : ks + 1, n_loads = ks == 0 ? 2 : 1;  // 0,1 | 2 | 3
-                if (STEADY) {
-#pragma unroll
-                    for (int r = 0; r < 6; ++r) {
-                        if (r == 0) issue_b_one(first_load);
-                        if (r == 3 && n_loads == 2) issue_b_one(first_load + 1);
-                        fetch_one(nxt, sa, sb, ks + 1, r);
-                    }
-                } else {
-                    if (flag) {
-                        issue_b_one(first_load);
-                        if (n_loads == 2) issue_b_one(first_load + 1);
-                    }
-                    fetch(nxt, sa, sb, ks + 1);
-                }
-            } else {
-                if (STEADY || flag) {
-                    advance_b();
-                    asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
-                } else {
-                    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-                }
-                asm volatile("s_barrier" ::: "memory");
-                if (STEADY) {
-#pragma unroll
-                    for (int r = 0; r < 6; ++r) {
-                        if (r < LOADS) issue_a_one(r);
-                        if (CROSS) fetch_one(nxt, sa_next, sb_next, 0, r);
-                    }
-                    advance_a();
-                } else {
-                    if (flag) issue_a();
-                    if (CROSS) fetch(nxt, sa_next, sb_next, 0);
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int jj = 0; jj < 2; ++jj)
-                    acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][jj], fa[cur][i], acc[i][jj], 0, 0, 0);
-            // issue order inside a group: the fragment reads of the next group and the direct-to-LDS
-            // loads are spread between the 8 MFMAs
-            if (STEADY && !last) {
-#pragma unroll
-                for (int r = 0; r < 6; ++r) {
-                    if (r == 0 || (r == 3 && ks == 0)) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // 1 VMEM
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                     // 1 MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                     // 1 LDS read
-                }
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            } else if (STEADY && last) {
-#pragma unroll
-                for (int r = 0; r < 8; ++r) {
-                    if (r < LOADS) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    if (CROSS && r < 6) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                }
-            } else if (!last) {
-                // tile boundary: the conditional loads sit in a basic block of their own
-#pragma unroll
-                for (int r = 0; r < 6; ++r) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                }
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-    // The step with v_mfma_f32_16x16x32_bf16: two K groups of 32 MFMAs each, in two passes: the eight
-    // activation fragments with weight fragments 0 and 1, then with 2 and 3.  Registers: the activation
-    // fragments live through the group; weight fragments 2 and 3 of a group are read during its first
-    // pass, and during the second pass the next group's weight fragments 0, 1 (into the registers pass one
-    // has freed) and its activation fragment i right after the current fragment i has had its last MFMA.
-    // The one wait + barrier of the step stands between its two groups, so the second group's weight
-    // fragments 2, 3 are read ahead of it as well (every read of the step's buffers precedes the barrier);
-    // the second group's second pass reads the next step's first fragments from the next buffers.
-    // RD_POS: fragment read r (r < 4 weight, else activation r - 4) is issued after the group's MFMA number ..
-    constexpr int RD_CUR_POS[2] = {0, 1};                                      // this group's weight fragments 2, 3
+    constexpr int RD_OWN23_POS[2] = {0, 1};                                    // this group's weight fragments 2, 3
     constexpr int RD_NXT[10] = {0, 1, 4, 5, 6, 7, 8, 9, 10, 11};               // next group: weights 0, 1, activations 0..7
     constexpr int RD_NXT_POS[10] = {16, 17, 18, 20, 22, 24, 26, 28, 30, 31};
-    constexpr int RD_NXT23_POS[2] = {19, 21};                                  // next group's weights 2, 3 (before a barrier)
-    constexpr int LD_POS[4] = {3, 7, 11, 15};                                  // direct-to-LDS loads of the step
-    auto mfma_group16 = [&](f32x4_t (&acc)[8][4], int cur) {
+    constexpr int RD_NXT23_POS[2] = {19, 21};                                  // next group's weights 2, 3 (ahead of the barrier)
+    constexpr int LD_POS[4] = {3, 7, 11, 15};
+    auto mfma_group = [&](f32x4_t (&acc)[8][4], int cur) {
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass)
 #pragma unroll
@@ -478,45 +372,45 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
 #pragma unroll
                 for (int jl = 0; jl < 2; ++jl) {
                     const int j = pass * 2 + jl;
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(gb[cur][j], ga[cur][i], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
                 }
     };
-    // reads and loads of one group in program order = issue order; `own23`: this group's weight fragments
-    // 2, 3 are still to be read (not so after a barrier); `next`: read the next group's fragments from
-    // (na, nb, ngk) into buffer nbuf, `next23` including its weight fragments 2, 3
-    auto group_reads16 = [&](int cur, const char *ca, const char *cb, int cgk, bool own23, bool next, bool next23, int nbuf,
-                             const char *na, const char *nb, int ngk, auto issue_one, bool loads) {
+    // Reads and loads of one group in program order = issue order wanted (direct loads and fragment reads
+    // both touch LDS, so the compiler keeps them in this order).  own23: this group's weight fragments
+    // 2, 3 are still to be read; next: read the next group's fragments from (na, nb, ngk) into buffer
+    // nbuf, next23: including its weight fragments 2, 3.
+    auto group_reads = [&](int cur, const char *ca, const char *cb, int cgk, bool own23, bool next, bool next23, int nbuf,
+                           const char *na, const char *nb, int ngk, auto issue_one) {
 #pragma unroll
         for (int m = 0; m < 32; ++m) {
             if (own23) {
 #pragma unroll
                 for (int q = 0; q < 2; ++q)
-                    if (RD_CUR_POS[q] == m) fetch16_one(cur, ca, cb, cgk, 2 + q);
+                    if (RD_OWN23_POS[q] == m) fetch_one(cur, ca, cb, cgk, 2 + q);
             }
             if (next) {
 #pragma unroll
                 for (int q = 0; q < 10; ++q)
-                    if (RD_NXT_POS[q] == m) fetch16_one(nbuf, na, nb, ngk, RD_NXT[q]);
+                    if (RD_NXT_POS[q] == m) fetch_one(nbuf, na, nb, ngk, RD_NXT[q]);
                 if (next23) {
 #pragma unroll
                     for (int q = 0; q < 2; ++q)
-                        if (RD_NXT23_POS[q] == m) fetch16_one(nbuf, na, nb, ngk, 2 + q);
+                        if (RD_NXT23_POS[q] == m) fetch_one(nbuf, na, nb, ngk, 2 + q);
                 }
             }
-            if (loads) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    if (LD_POS[q] == m) issue_one(q);
-            }
+            for (int q = 0; q < 4; ++q)
+                if (LD_POS[q] == m) issue_one(q);
         }
     };
-    auto group_sched16 = [&](bool own23, bool next, bool next23, bool loads) {
+    // the same order for the instruction scheduler: after every MFMA the reads and the load placed there
+    auto group_sched = [&](bool own23, bool next, bool next23) {
 #pragma unroll
         for (int m = 0; m < 32; ++m) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
             int reads = 0;
             if (own23)
-                for (int q = 0; q < 2; ++q) reads += RD_CUR_POS[q] == m;
+                for (int q = 0; q < 2; ++q) reads += RD_OWN23_POS[q] == m;
             if (next) {
                 for (int q = 0; q < 10; ++q) reads += RD_NXT_POS[q] == m;
                 if (next23)
@@ -524,122 +418,55 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
             }
             if (reads == 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS reads
             if (reads == 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            if (loads) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    if (LD_POS[q] == m) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);   // 1 VMEM
-            }
+            for (int q = 0; q < 4; ++q)
+                if (LD_POS[q] == m) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);   // 1 VMEM
         }
         __builtin_amdgcn_sched_barrier(0);
     };
-    auto step16 = [&](f32x4_t (&acc)[8][4], auto load_mode, auto cross, bool flag) {
-        constexpr int LOAD_MODE = decltype(load_mode)::value;
-        constexpr bool CROSS = decltype(cross)::value, STEADY = LOAD_MODE == 1;
+    auto step = [&](f32x4_t (&acc)[8][4], auto cross) {
+        constexpr bool CROSS = decltype(cross)::value;
         const char *sa = smem + a_con * A_BYTES, *sb = smem + B_BASE + b_con * B_BYTES;
         a_con ^= 1;
         b_con = (b_con + 1 == NBUF_B) ? 0 : b_con + 1;
         const char *sa_next = smem + a_con * A_BYTES, *sb_next = smem + B_BASE + b_con * B_BYTES;
-        // ---- first K group: weight loads of step g + 2; reads of this step's second group ----
-        if (!STEADY && flag) {   // tile boundary: the conditional loads sit in a basic block of their own
-#pragma unroll
-            for (int q = 0; q < 4; ++q) issue_b_one(q);
-        }
-        group_reads16(0, sa, sb, 0, true, true, true, 1, sa, sb, 1, issue_b_one, STEADY);
-        mfma_group16(acc, 0);
-        group_sched16(true, true, true, STEADY);
-        // ---- second K group ----
-        if (STEADY || flag) {
-            advance_b();
-            asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
-        } else {
-            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-        }
+        group_reads(0, sa, sb, 0, true, true, true, 1, sa, sb, 1, issue_b_one);
+        mfma_group(acc, 0);
+        group_sched(true, true, true);
+        advance_b();
+        asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
         asm volatile("s_barrier" ::: "memory");
-        if (!STEADY && flag) issue_a();
-        group_reads16(1, sa, sb, 1, false, CROSS, false, 0, sa_next, sb_next, 0, issue_a_one, STEADY);
-        if (STEADY) advance_a();
-        mfma_group16(acc, 1);
-        group_sched16(false, CROSS, false, STEADY);
+        group_reads(1, sa, sb, 1, false, CROSS, false, 0, sa_next, sb_next, 0, issue_a_one);
+        advance_a();
+        mfma_group(acc, 1);
+        group_sched(false, CROSS, false);
     };
     // the same step for a wavefront with no valid rows in this tile: synchronise and load only
-    auto idle_step = [&](bool loads_on) {
+    auto idle_step = [&]() {
         a_con ^= 1;
         b_con = (b_con + 1 == NBUF_B) ? 0 : b_con + 1;
-        if (loads_on) {
-            issue_b();
-            asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
-        } else {
-            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-        }
+        issue_b();
+        asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
         asm volatile("s_barrier" ::: "memory");
-        if (loads_on) issue_a();
+        issue_a();
     };
     using T_ = std::integral_constant<bool, true>;
     using F_ = std::integral_constant<bool, false>;
-    using M1_ = std::integral_constant<int, 1>;
-    using M2_ = std::integral_constant<int, 2>;
 
     // ---- epilogue ---------------------------------------------------------------------------------
-    // The weight fragment is the MFMA's first operand, so acc[i][jj] holds a transposed 32x32 tile:
-    // element v of lane l is (n = 8*(v/4) + 4*(l/32) + v%4, m = l%32), i.e. four consecutive output
-    // columns of one row per group of four values.  Per 32-row sub-tile the wavefront packs to
-    // bf16, transposes through LDS (16-byte chunks XOR-swizzled by row) and writes whole rows with
-    // 16-byte stores.  The staging bytes are the four 1 KB pieces of the free weight buffer that this
-    // wavefront's own next weight loads fill, so no other wavefront touches them.
+    // The weight fragment is the MFMA's first operand, so acc[i][j] holds a transposed 16x16 block (rows
+    // 16 i .., columns 16 j ..; FUSED_UP: j < 2 gate, j >= 2 the up projection of the same columns):
+    // element v of lane l is (n = 4 * (l / 16) + v, m = l % 16), i.e. four consecutive output columns of
+    // one row.  Per 32-row sub-tile (two blocks i) the wavefront packs to bf16, transposes through LDS
+    // (16-byte chunks XOR-swizzled by row) and writes whole rows with 16-byte stores.  The staging bytes
+    // are the four 1 KB pieces of the free weight buffer that this wavefront's own next weight loads
+    // fill, so no other wavefront touches them.
     constexpr int BNW = SH::BNW, ROWB = SH::ROWB;
     constexpr int CH = ROWB / 16;               // 16-byte chunks per staged row
     constexpr int KSH = (ROWB == 128) ? 1 : 2;  // rows per 256 bytes of LDS = 1 << KSH
     // byte o of the wavefront's logical 4 KB staging area -> offset inside a weight buffer
     auto stg_off = [&](int o) { return wave * 1024 + (o >> 10) * 8192 + (o & 1023); };
-    auto epilogue = [&](f32x16_t (&acc)[4][2], const Tile &t, int n0, int n_valid) {
-        uint16_t *out = (uint16_t *)g.out;
-        constexpr int ROWS_PER_IT = 64 / CH;
-        const int el = opaque_lane(), frow = el & 31, fhalf8 = (el >> 5) * 8;  // not kept across the K loop
-        const int rr = el / CH, cc = el % CH;
-        const int ncol = n0 + wn * BNW + cc * 8;
-        const int wkey = (frow >> KSH) & (CH - 1);
-        char *stg = smem + B_BASE + b_iss * B_BYTES;  // the buffer read in the tile's last step
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (i >= n_valid) break;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (FUSED_UP) {
-                    float h[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const float gt = acc[i][0][q * 4 + r], up = acc[i][1][q * 4 + r];
-                        h[r] = gt * __frcp_rn(1.0f + __expf(-gt)) * up;
-                    }
-                    uint2 pk = make_uint2(pack_bf16x2(h[0], h[1]), pack_bf16x2(h[2], h[3]));
-                    *(uint2 *)(stg + stg_off(frow * ROWB + ((q ^ wkey) * 16) + fhalf8)) = pk;
-                } else {
-#pragma unroll
-                    for (int jj = 0; jj < 2; ++jj) {
-                        uint2 pk = make_uint2(pack_bf16x2(acc[i][jj][q * 4 + 0], acc[i][jj][q * 4 + 1]),
-                                              pack_bf16x2(acc[i][jj][q * 4 + 2], acc[i][jj][q * 4 + 3]));
-                        *(uint2 *)(stg + stg_off(frow * ROWB + (((jj * 4 + q) ^ wkey) * 16) + fhalf8)) = pk;
-                    }
-                }
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wavefront's own writes, read back below
-#pragma unroll
-            for (int it = 0; it < 32 / ROWS_PER_IT; ++it) {
-                const int ml = it * ROWS_PER_IT + rr;
-                const int row = t.m0 + wm * 128 + i * 32 + ml;
-                const int key = (ml >> KSH) & (CH - 1);
-                const uint4 v = *(const uint4 *)(stg + stg_off(ml * ROWB + ((cc ^ key) * 16)));
-                if (row < t.m_end && ncol < g.N) *(uint4 *)(out + (int64_t)row * g.ldo + ncol) = v;
-            }
-            // LDS operations of one wavefront execute in order: the next sub-tile's writes cannot
-            // overtake these reads
-        }
-    };
-
-    // The same for the 16x16 blocks of v_mfma_f32_16x16x32_bf16: acc[i][j] holds element v of lane l at
-    // (n = 4 * (l / 16) + v, m = l % 16) of block (rows 16 i .., columns 16 j ..); FUSED_UP: j < 2 gate, j >= 2
-    // the up projection of the same columns.  Two blocks i make one staged 32-row sub-tile.
-    auto epilogue16 = [&](f32x4_t (&acc)[8][4], const Tile &t, int n0, int n_valid) {
+    auto epilogue = [&](f32x4_t (&acc)[8][4], const Tile &t, int n0, int n_valid) {
         uint16_t *out = (uint16_t *)g.out;
         constexpr int ROWS_PER_IT = 64 / CH;
         const int el = opaque_lane(), er = el & 15, eq = el >> 4;   // not kept across the K loop
@@ -679,12 +506,15 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
                 const uint4 v = *(const uint4 *)(stg + stg_off(ml * ROWB + ((cc ^ key) * 16)));
                 if (row < t.m_end && ncol < g.N) *(uint4 *)(out + (int64_t)row * g.ldo + ncol) = v;
             }
+            // LDS operations of one wavefront execute in order: the next sub-tile's writes cannot
+            // overtake these reads
         }
     };
 
     // ---- tile loop ----------------------------------------------------------------------------------
     // Per tile of nk steps: steps 0 .. nk-3 load this tile's steps 2 .. nk-1; steps nk-2 and nk-1
-    // load steps 0 and 1 of the next tile, if there is one.
+    // load steps 0 and 1 of the next tile, or, for the workgroup's last tile, of this tile again (valid
+    // addresses, nobody reads the data), so that every step is the same straight code.
     int cur_mt, cur_n0;
     job_tile(job, cur_mt, cur_n0);
     Tile cur = lookup(cur_mt);
@@ -708,7 +538,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
         }
         // 32-row sub-tiles of this wavefront that hold at least one valid row (scalar)
         const int n_valid = max(0, min(4, (cur.m_end - (cur.m0 + wm * 128) + 31) / 32));
-        if (n_valid > 0 && M16) {
+        if (n_valid > 0) {
             f32x4_t acc[8][4];
 #pragma unroll
             for (int i = 0; i < 8; ++i)
@@ -716,59 +546,32 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
-            fetch16(0, smem + a_con * A_BYTES, smem + B_BASE + b_con * B_BYTES, 0);
+            fetch_entry(0, smem + a_con * A_BYTES, smem + B_BASE + b_con * B_BYTES, 0);
             for (int kt = 0; kt + 2 < nk; ++kt) {
                 const bool copy_now = COPY && (kt % SC_PERIOD) == 0;
                 if (copy_now) copy_issue();
-                step16(acc, M1_{}, T_{}, true);
+                step(acc, T_{});
                 if (copy_now) copy_store();
             }
-            // the last two steps load the first two of the next tile; without one they load this tile's
-            // again (valid addresses, nobody reads them), so that every step is the same straight code
             set_a_sources(nxt);
             set_b_sources(nxt, nxt_n0);
-            step16(acc, M1_{}, T_{}, true);
-            step16(acc, M1_{}, F_{}, true);
-            epilogue16(acc, cur, cur_n0, n_valid);
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // staging reads done before the buffer is refilled
-        } else if (n_valid > 0) {
-            f32x16_t acc[4][2];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[i][jj][v] = 0.0f;
-            fetch(0, smem + a_con * A_BYTES, smem + B_BASE + b_con * B_BYTES, 0);
-            for (int kt = 0; kt + 2 < nk; ++kt) {
-                const bool copy_now = COPY && (kt % SC_PERIOD) == 0;
-                if (copy_now) copy_issue();
-                step(acc, M1_{}, T_{}, true);
-                if (copy_now) copy_store();
-            }
-            if (has_next) {
-                set_a_sources(nxt);
-                set_b_sources(nxt, nxt_n0);
-            }
-            step(acc, M2_{}, T_{}, has_next);
-            step(acc, M2_{}, F_{}, has_next);
+            step(acc, T_{});
+            step(acc, F_{});
             epilogue(acc, cur, cur_n0, n_valid);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // staging reads done before the buffer is refilled
         } else {
-            for (int kt = 0; kt + 2 < nk; ++kt) idle_step(true);
-            if (has_next || M16) {
-                set_a_sources(nxt);
-                set_b_sources(nxt, nxt_n0);
-            }
-            idle_step(has_next || M16);
-            idle_step(has_next || M16);
+            for (int kt = 0; kt + 2 < nk; ++kt) idle_step();
+            set_a_sources(nxt);
+            set_b_sources(nxt, nxt_n0);
+            idle_step();
+            idle_step();
         }
         if (!has_next) break;
         cur = nxt;
         cur_n0 = nxt_n0;
         job = next_job;
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no load may still be on its way to LDS when the workgroup ends
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no load may still be on its way to LDS when the workgroup ends
     if (COPY) copy_rest();
 }
 
