@@ -57,8 +57,6 @@ namespace pers {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef const __attribute__((address_space(1))) void global_void_t;
 
 constexpr int BM = 256, BROWS = 256, THREADS = 512, N_XCD = 8;
 constexpr int BK = 64;
