@@ -77,7 +77,7 @@ static int launch_gemm(const GemmArgs &g, grace_dtype dt, int64_t m_bound, hipSt
         using SH = pers::Shape<FUSED_UP>;
         const int ntn = (g.N + SH::BN - 1) / SH::BN;
         const int grid = pers::grid_blocks(n_cu);
-        if ((m_bound / pers::BM + n_seg) * (int64_t)ntn > INT32_MAX) return fail(GRACE_ESHAPE, "%s: too many tiles", what);
+        if ((m_bound / 160 + n_seg) * (int64_t)ntn > INT32_MAX) return fail(GRACE_ESHAPE, "%s: too many tiles", what);   // the lowest m-tile has 160 rows
         if (n_seg <= 64) {
             if (!allow_full_lds((const void *)pers::gemm_bf16_persist_kernel<FUSED_UP, 1, WHO>, what)) return GRACE_EHIP;
             pers::gemm_bf16_persist_kernel<FUSED_UP, 1, WHO><<<grid, pers::THREADS, pers::LDS_BYTES, st>>>(g, ntn);

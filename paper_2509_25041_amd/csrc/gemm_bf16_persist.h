@@ -98,21 +98,25 @@ __device__ __forceinline__ void load16_to_lds(const char *base, uint32_t voff, c
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0" ::"s"(base), "v"(voff), "s"(lds_addr) : "memory");
 }
 
-// SEG_PER_LANE: 1 for up to 64 row segments, 4 for up to 256.  WHO only names the instantiation
-// (EXPERTS: grouped expert FFN, SHARED: always-on shared experts), so that a kernel trace lists the
-// two uses separately.
 enum Who { EXPERTS = 0, SHARED = 1 };
-template <bool FUSED_UP, int SEG_PER_LANE, Who WHO>
-__global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const GemmArgs g, int n_tiles_n) {
+
+// HF: activation fragments (of 16 rows) per wavefront, i.e. the m-tile holds 32 * HF rows, HF * 16 for each
+// of the two wavefront rows.  8 is the full tile; 7, 6, 5 make tiles of 224, 192, 160 rows whose K loop
+// has proportionally fewer MFMAs (the weight tile and the loads stay the same).  The kernel picks, from
+// the row segments it finds on the device, the height whose tile count fills whole rounds of the grid
+// best (tile_height below).
+template <bool FUSED_UP, int SEG_PER_LANE, Who WHO, int HF>
+__device__ __forceinline__ void persist_body(const GemmArgs g, int n_tiles_n, SegTable<SEG_PER_LANE> &segs) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
+    static_assert(HF >= 5 && HF <= 8, "schedule positions below assume 5 to 8 fragments");
     using SH = Shape<FUSED_UP>;
     constexpr int BN = SH::BN;
+    constexpr int HALF_ROWS = HF * 16, TILE_ROWS = 2 * HALF_ROWS;
     const int tid = (int)threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar
     const int wm = wave >> 2, wn = wave & 3;
 
-    SegTable<BM, SEG_PER_LANE> segs;
-    segs.init(g, lane);
+    segs.cut(lane, TILE_ROWS);
     const int total_mt = segs.total;
     auto lookup = [&](int mt) { return segs.lookup(mt, lane); };
 
@@ -318,12 +322,12 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     // per wavefront and group 4 weight fragments (FUSED_UP: two of the gate rows, two of the up rows)
     // and 8 activation fragments.
     const int frow = lane & 15, fkey = swizzle_key(frow);
-    const int a_base = (wm * 128 + frow) * ROW_BYTES;
+    const int a_base = (wm * HALF_ROWS + frow) * ROW_BYTES;
     const int b_base = ((FUSED_UP ? wn * 32 : wn * 64) + frow) * ROW_BYTES;
     int pc[2];
 #pragma unroll
     for (int gk = 0; gk < 2; ++gk) pc[gk] = ((gk * 4 + (lane >> 4)) ^ fkey) * 16;
-    bf16x8_t fa[2][8], fb[2][4];
+    bf16x8_t fa[2][HF], fb[2][4];
     // fragment r of a K group: r < 4 weight rows, else activation rows
     auto fetch_one = [&](int buf, const char *sa, const char *sb, int gk, int r) {
         if (r < 4) {
@@ -336,7 +340,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     // what a K group needs on entry: its activation fragments and weight fragments 0, 1
     auto fetch_entry = [&](int buf, const char *sa, const char *sb, int gk) {
 #pragma unroll
-        for (int r = 0; r < 12; ++r)
+        for (int r = 0; r < 4 + HF; ++r)
             if (r < 2 || r >= 4) fetch_one(buf, sa, sb, gk, r);
     };
 
@@ -357,16 +361,18 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     // across a tile boundary, where the registers are needed for the epilogue).
     // RD_*_POS: the read is issued after the group's MFMA number ..; LD_POS likewise for the four loads.
     int a_con = 0, b_con = 0;  // buffers the current step reads
+    constexpr int NM = 4 * HF;                                                 // MFMAs per K group
     constexpr int RD_OWN23_POS[2] = {0, 1};                                    // this group's weight fragments 2, 3
-    constexpr int RD_NXT[10] = {0, 1, 4, 5, 6, 7, 8, 9, 10, 11};               // next group: weights 0, 1, activations 0..7
-    constexpr int RD_NXT_POS[10] = {16, 17, 18, 20, 22, 24, 26, 28, 30, 31};
-    constexpr int RD_NXT23_POS[2] = {19, 21};                                  // next group's weights 2, 3 (ahead of the barrier)
+    constexpr int RD_NXT23_POS[2] = {2 * HF + 3, 2 * HF + 5};                  // next group's weights 2, 3 (ahead of the barrier)
     constexpr int LD_POS[4] = {3, 7, 11, 15};
-    auto mfma_group = [&](f32x4_t (&acc)[8][4], int cur) {
+    // next group: weight fragments 0, 1 when pass one is over, activation fragment i after the last MFMA of
+    // the current fragment i (number 2 HF + 2 i + 1), the last one after the last MFMA but one
+    auto rd_nxt_pos = [](int r) { return r < 2 ? 2 * HF + r : (r - 4 == HF - 1 ? NM - 1 : 2 * HF + 2 + 2 * (r - 4)); };
+    auto mfma_group = [&](f32x4_t (&acc)[HF][4], int cur) {
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass)
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
+            for (int i = 0; i < HF; ++i)
 #pragma unroll
                 for (int jl = 0; jl < 2; ++jl) {
                     const int j = pass * 2 + jl;
@@ -380,7 +386,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     auto group_reads = [&](int cur, const char *ca, const char *cb, int cgk, bool own23, bool next, bool next23, int nbuf,
                            const char *na, const char *nb, int ngk, auto issue_one) {
 #pragma unroll
-        for (int m = 0; m < 32; ++m) {
+        for (int m = 0; m < NM; ++m) {
             if (own23) {
 #pragma unroll
                 for (int q = 0; q < 2; ++q)
@@ -388,8 +394,8 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
             }
             if (next) {
 #pragma unroll
-                for (int q = 0; q < 10; ++q)
-                    if (RD_NXT_POS[q] == m) fetch_one(nbuf, na, nb, ngk, RD_NXT[q]);
+                for (int r = 0; r < 4 + HF; ++r)
+                    if ((r < 2 || r >= 4) && rd_nxt_pos(r) == m) fetch_one(nbuf, na, nb, ngk, r);
                 if (next23) {
 #pragma unroll
                     for (int q = 0; q < 2; ++q)
@@ -404,13 +410,13 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     // the same order for the instruction scheduler: after every MFMA the reads and the load placed there
     auto group_sched = [&](bool own23, bool next, bool next23) {
 #pragma unroll
-        for (int m = 0; m < 32; ++m) {
+        for (int m = 0; m < NM; ++m) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
             int reads = 0;
             if (own23)
                 for (int q = 0; q < 2; ++q) reads += RD_OWN23_POS[q] == m;
             if (next) {
-                for (int q = 0; q < 10; ++q) reads += RD_NXT_POS[q] == m;
+                for (int r = 0; r < 4 + HF; ++r) reads += (r < 2 || r >= 4) && rd_nxt_pos(r) == m;
                 if (next23)
                     for (int q = 0; q < 2; ++q) reads += RD_NXT23_POS[q] == m;
             }
@@ -422,7 +428,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
         }
         __builtin_amdgcn_sched_barrier(0);
     };
-    auto step = [&](f32x4_t (&acc)[8][4], auto cross) {
+    auto step = [&](f32x4_t (&acc)[HF][4], auto cross) {
         constexpr bool CROSS = decltype(cross)::value;
         const char *sa = smem + a_con * A_BYTES, *sb = smem + B_BASE + b_con * B_BYTES;
         a_con ^= 1;
@@ -464,7 +470,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     constexpr int KSH = (ROWB == 128) ? 1 : 2;  // rows per 256 bytes of LDS = 1 << KSH
     // byte o of the wavefront's logical 4 KB staging area -> offset inside a weight buffer
     auto stg_off = [&](int o) { return wave * 1024 + (o >> 10) * 8192 + (o & 1023); };
-    auto epilogue = [&](f32x4_t (&acc)[8][4], const Tile &t, int n0, int n_valid) {
+    auto epilogue = [&](f32x4_t (&acc)[HF][4], const Tile &t, int n0, int n_valid) {
         uint16_t *out = (uint16_t *)g.out;
         constexpr int ROWS_PER_IT = 64 / CH;
         const int el = opaque_lane(), er = el & 15, eq = el >> 4;   // not kept across the K loop
@@ -472,11 +478,12 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
         const int ncol = n0 + wn * BNW + cc * 8;
         char *stg = smem + B_BASE + b_iss * B_BYTES;  // the buffer read in the tile's last step
 #pragma unroll
-        for (int i32 = 0; i32 < 4; ++i32) {
+        for (int i32 = 0; i32 < (HF + 1) / 2; ++i32) {
             if (i32 >= n_valid) break;
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub) {
                 const int i = i32 * 2 + sub, row = sub * 16 + er;
+                if (i >= HF) continue;   // an odd number of blocks: the last sub-tile has 16 rows
                 const int wkey = (row >> KSH) & (CH - 1);
 #pragma unroll
                 for (int jn = 0; jn < (FUSED_UP ? 2 : 4); ++jn) {
@@ -499,10 +506,11 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
 #pragma unroll
             for (int it = 0; it < 32 / ROWS_PER_IT; ++it) {
                 const int ml = it * ROWS_PER_IT + rr;
-                const int row = t.m0 + wm * 128 + i32 * 32 + ml;
+                const int hrow = i32 * 32 + ml;                 // row inside the wavefront's half of the tile
+                const int row = t.m0 + wm * HALF_ROWS + hrow;
                 const int key = (ml >> KSH) & (CH - 1);
                 const uint4 v = *(const uint4 *)(stg + stg_off(ml * ROWB + ((cc ^ key) * 16)));
-                if (row < t.m_end && ncol < g.N) *(uint4 *)(out + (int64_t)row * g.ldo + ncol) = v;
+                if (hrow < HALF_ROWS && row < t.m_end && ncol < g.N) *(uint4 *)(out + (int64_t)row * g.ldo + ncol) = v;
             }
             // LDS operations of one wavefront execute in order: the next sub-tile's writes cannot
             // overtake these reads
@@ -535,11 +543,11 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
             nxt = lookup(nxt_mt);
         }
         // 32-row sub-tiles of this wavefront that hold at least one valid row (scalar)
-        const int n_valid = max(0, min(4, (cur.m_end - (cur.m0 + wm * 128) + 31) / 32));
+        const int n_valid = max(0, min((HF + 1) / 2, (cur.m_end - (cur.m0 + wm * HALF_ROWS) + 31) / 32));
         if (n_valid > 0) {
-            f32x4_t acc[8][4];
+            f32x4_t acc[HF][4];
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
+            for (int i = 0; i < HF; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -571,6 +579,47 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const Gem
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no load may still be on its way to LDS when the workgroup ends
     if (COPY) copy_rest();
+}
+
+// Rows per m-tile for this launch, as fragments per wavefront (8, 7, 6 or 5).  Tiles are dealt to the
+// grid in whole rounds, so 2.6 rounds of full tiles cost 3; lower tiles are more but cheaper, and the
+// height whose rounds x cost is smallest wins (ties to the higher tile).  Cost of a tile of HF
+// fragments per wavefront relative to the full one: (HF + 2) / 10 (the weight tile's loads and the
+// per-tile overheads do not shrink).  Every workgroup computes the same answer from the row segments
+// on the device, from one read of their bounds.
+template <int SEG_PER_LANE>
+__device__ __forceinline__ int tile_height(const SegTable<SEG_PER_LANE> &segs, int n_tiles_n) {
+    int best_hf = 8, best_cost = 0x7fffffff;
+#pragma unroll
+    for (int hf = 8; hf >= 5; --hf) {
+        const int tiles = segs.count(32 * hf) * n_tiles_n;
+        const int rounds = (tiles + (int)gridDim.x - 1) / (int)gridDim.x;
+        const int cost = rounds * (hf + 2);
+        if (cost < best_cost) { best_cost = cost; best_hf = hf; }
+    }
+    return best_hf;
+}
+
+// SEG_PER_LANE: 1 for up to 64 row segments, 4 for up to 256.  WHO only names the instantiation
+// (EXPERTS: grouped expert FFN, SHARED: always-on shared experts), so that a kernel trace lists the
+// two uses separately.
+template <bool FUSED_UP, int SEG_PER_LANE, Who WHO>
+__global__ __launch_bounds__(THREADS, 1) void gemm_bf16_persist_kernel(const GemmArgs g, int n_tiles_n) {
+    SegTable<SEG_PER_LANE> segs;
+    segs.load(g, (int)threadIdx.x & 63);
+    // Lower tiles only for the experts' down projection: measured, they pay there (mixtral 258 -> 226 us,
+    // qwen3moe 62 -> 55 us) and not for the gate+up projection, whose tile time hardly falls with its row
+    // count; the shared experts' single segment of T rows fills its rounds with full tiles anyway.
+    if constexpr (!FUSED_UP && WHO == EXPERTS) {
+        switch (tile_height<SEG_PER_LANE>(segs, n_tiles_n)) {   // uniform over the grid
+            case 8: persist_body<FUSED_UP, SEG_PER_LANE, WHO, 8>(g, n_tiles_n, segs); break;
+            case 7: persist_body<FUSED_UP, SEG_PER_LANE, WHO, 7>(g, n_tiles_n, segs); break;
+            case 6: persist_body<FUSED_UP, SEG_PER_LANE, WHO, 6>(g, n_tiles_n, segs); break;
+            default: persist_body<FUSED_UP, SEG_PER_LANE, WHO, 5>(g, n_tiles_n, segs); break;
+        }
+    } else {
+        persist_body<FUSED_UP, SEG_PER_LANE, WHO, 8>(g, n_tiles_n, segs);
+    }
 }
 
 // Workgroups to launch on a device with `n_cu` compute units: one per compute unit, a multiple of 8.

@@ -93,20 +93,21 @@ __device__ __forceinline__ bool locate_tile(const GemmArgs &g, int mt, int &slot
     return false;
 }
 
-// Row segments (one per local expert slot) cut into m-tiles of BM rows, held in registers by every
+// Row segments (one per local expert slot) cut into m-tiles of bm rows, held in registers by every
 // wavefront: lane l keeps segments SPL * l .. SPL * l + SPL - 1 (so at most 64 * SPL segments) and
 // the index of their first m-tile.  A tile's segment is found with a ballot; no table in memory.
 struct Tile {
-    int slot, m0, m_end;  // segment, first row, end of the segment
+    int slot, m0, m_end;  // segment, first row, end of the tile's rows (the segment's end for its last tile)
 };
 
-template <int BM, int SPL>
+template <int SPL>
 struct SegTable {
     int lo[SPL], hi[SPL], base[SPL];
     int total;  // m-tiles over all segments (scalar)
+    int bm;     // rows per m-tile (scalar)
 
-    __device__ __forceinline__ void init(const GemmArgs &g, int lane) {
-        int lane_tiles = 0;
+    // first: the segments' bounds, read once
+    __device__ __forceinline__ void load(const GemmArgs &g, int lane) {
 #pragma unroll
         for (int q = 0; q < SPL; ++q) {
             const int s = lane * SPL + q;
@@ -118,8 +119,27 @@ struct SegTable {
             }
             lo[q] = l;
             hi[q] = h;
-            base[q] = lane_tiles;                 // made global below
-            lane_tiles += (h - l + BM - 1) / BM;  // h >= l
+        }
+    }
+
+    // m-tiles of `rows_per_tile` rows over all segments (scalar); changes nothing
+    __device__ __forceinline__ int count(int rows_per_tile) const {
+        int lane_tiles = 0;
+#pragma unroll
+        for (int q = 0; q < SPL; ++q) lane_tiles += (hi[q] - lo[q] + rows_per_tile - 1) / rows_per_tile;
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) lane_tiles += __shfl_xor(lane_tiles, o, 64);
+        return __builtin_amdgcn_readfirstlane(lane_tiles);
+    }
+
+    // then: cut into m-tiles of `rows_per_tile` rows
+    __device__ __forceinline__ void cut(int lane, int rows_per_tile) {
+        bm = rows_per_tile;
+        int lane_tiles = 0;
+#pragma unroll
+        for (int q = 0; q < SPL; ++q) {
+            base[q] = lane_tiles;                         // made global below
+            lane_tiles += (hi[q] - lo[q] + bm - 1) / bm;  // hi >= lo
         }
         int incl = lane_tiles;
 #pragma unroll
@@ -133,19 +153,19 @@ struct SegTable {
         total = __builtin_amdgcn_readlane(incl, 63);
     }
 
-    // (slot, first row, segment end) of m-tile mt < total, as scalars
+    // (slot, first row, end of the tile's rows) of m-tile mt < total, as scalars
     __device__ __forceinline__ Tile lookup(int mt, int lane) const {
         int slot = 0, m0 = 0, m_end = 0;
         bool hit = false;
 #pragma unroll
         for (int q = 0; q < SPL; ++q) {
             const int rel = mt - base[q];
-            const int tiles = (hi[q] - lo[q] + BM - 1) / BM;
+            const int tiles = (hi[q] - lo[q] + bm - 1) / bm;
             if (rel >= 0 && rel < tiles) {
                 hit = true;
                 slot = lane * SPL + q;
-                m0 = lo[q] + rel * BM;
-                m_end = hi[q];
+                m0 = lo[q] + rel * bm;
+                m_end = min(hi[q], m0 + bm);
             }
         }
         const unsigned long long owners = __ballot(hit);
