@@ -492,6 +492,53 @@ def test_more_than_64_local_slots_element_by_element():
     assert rel_err(oracle.widen(host(y))[lo:hi], want[lo:hi]) <= TOL["bf16"]
 
 
+def _chosen_tile_height(seg_rows, n_tiles_n, grid):
+    """The down projection's rule for its m-tile height (fragments of 16 rows per wavefront): the height
+    with the smallest rounds x (HF + 2), ties to the higher tile."""
+    best = None
+    for hf in (8, 7, 6, 5):
+        tiles = sum(-(-int(m) // (32 * hf)) for m in seg_rows) * n_tiles_n
+        cost = -(-tiles // grid) * (hf + 2)
+        if best is None or cost < best[0]:
+            best = (cost, hf)
+    return best[1]
+
+
+@pytest.mark.parametrize("want_hf,seg_rows", [
+    (8, [26000, 3000, 777, 1, 0, 900]),        # 256-row tiles fill one round of 256 workgroups (d = 512: 2 n-tiles)
+    (7, [22000, 3000, 777, 1, 0, 900]),        # 224-row tiles still fit one round: cheaper than 256-row tiles
+    (6, [18000, 3000, 777, 1, 0, 900]),        # 192-row tiles
+    (5, [12000, 3000, 777, 1, 0, 900]),        # 160-row tiles
+])
+def test_expert_down_projection_every_tile_height(want_hf, seg_rows):
+    """The expert down projection picks its m-tile height (256, 224, 192 or 160 rows) from the row
+    segments it finds on the device; one case per height, ragged segments (an empty one, one of a single
+    row), every element of the FFN against the oracle."""
+    d, f, k = 512, 128, 1
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    grid = max(8, n_cu // 8 * 8)
+    assert _chosen_tile_height(seg_rows, d // 256, grid) == want_hf or grid != 256
+    E = len(seg_rows)
+    rows = int(sum(seg_rows))
+    rng = np.random.default_rng(100 + want_hf)
+    table = grace.GraceTable(E, 1, 1, [0], [1], list(range(E + 1)), [0] * E)      # every expert once, on the one rank
+    xp = torch.from_numpy(rng.standard_normal((rows, d)).astype(np.float32)).cuda().to(torch.bfloat16)
+    wg = torch.from_numpy((0.05 * rng.standard_normal((E, f, d))).astype(np.float32)).cuda().to(torch.bfloat16)
+    wu = torch.from_numpy((0.05 * rng.standard_normal((E, f, d))).astype(np.float32)).cuda().to(torch.bfloat16)
+    wd = torch.from_numpy((0.05 * rng.standard_normal((E, d, f))).astype(np.float32)).cuda().to(torch.bfloat16)
+    off = np.concatenate([[0], np.cumsum(seg_rows)]).astype(np.int32)
+    y = grace.grace_expert_ffn(table, 0, xp, torch.from_numpy(off).cuda(), rows, k, wg, wu, wd)
+    torch.cuda.synchronize()
+    x64, got = oracle.widen(host(xp)), oracle.widen(host(y))
+    for e in range(E):
+        lo, hi = int(off[e]), int(off[e + 1])
+        if hi == lo:
+            continue
+        want = oracle.ffn_rows(x64[lo:hi], oracle.widen(host(wg[e])), oracle.widen(host(wu[e])), oracle.widen(host(wd[e])),
+                               threads=8)
+        assert rel_err(got[lo:hi], want) <= TOL["bf16"], (want_hf, e)
+
+
 @pytest.mark.parametrize("T,d,f,n_shared,k,dtype", [
     (3000, 512, 384, 2, 6, "bf16"),     # 1 KB rows, 12 row tiles x 6 column tiles: every workgroup has K steps to copy in
     (300, 4096, 128, 1, 3, "bf16"),     # 8 KB rows, 2 tiles for 256 workgroups: nearly all rows moved after the tile loop
