@@ -39,6 +39,13 @@
 // Preconditions (checked by the launcher): K and the K segment length are
 // multiples of 64, K >= 128, at most 256 segments, grid a multiple of 8.
 //
+// Tiles are dealt to the grid in whole rounds, so a tile count just above a
+// multiple of the grid wastes most of a round.  The experts' down projection
+// therefore exists for m-tiles of 256, 224, 192 and 160 rows (8, 7, 6, 5
+// activation fragments per wavefront; the weight tile stays 256 rows) and picks
+// the height on the device, from the segment lengths of the launch
+// (tile_height).
+//
 // Tile order is XCD-aware: workgroups are dealt round-robin to the 8 XCDs, so
 // block b runs on XCD b % 8 (checked with HW_REG_XCC_ID).  Each XCD owns a
 // contiguous range of m-tiles and its workgroups take consecutive (m-tile,
