@@ -185,7 +185,10 @@ __device__ __forceinline__ void persist_body(const GemmArgs g, int n_tiles_n, Se
     // two are independent.  Every wavefront therefore moves SC_NU 1 KB pieces of token rows every
     // SC_PERIOD-th K step: the pieces and their tokens' k positions are loaded just before a K step (so they are
     // older than the step's four weight loads and have landed when the step's wait has passed) and
-    // stored to the k rows right after it.  Pieces are dealt round-robin to all wavefronts of the grid;
+    // stored to the k rows right behind that wait and the barrier, in the middle of the step: vmcnt counts
+    // stores too, so the next step's wait has to see them acknowledged, and from there they have a whole
+    // step for it (issued after the step they had half of one, which cost 15-20 us more on the same
+    // workload).  Pieces are dealt round-robin to all wavefronts of the grid;
     // whatever is left when a wavefront runs out of K steps is moved at the end, so the scatter is
     // complete whatever the tile count.
     constexpr bool COPY = FUSED_UP && WHO == SHARED;
@@ -435,7 +438,7 @@ __device__ __forceinline__ void persist_body(const GemmArgs g, int n_tiles_n, Se
         }
         __builtin_amdgcn_sched_barrier(0);
     };
-    auto step = [&](f32x4_t (&acc)[HF][4], auto cross) {
+    auto step = [&](f32x4_t (&acc)[HF][4], auto cross, bool store_copy = false) {
         constexpr bool CROSS = decltype(cross)::value;
         const char *sa = smem + a_con * A_BYTES, *sb = smem + B_BASE + b_con * B_BYTES;
         a_con ^= 1;
@@ -447,6 +450,9 @@ __device__ __forceinline__ void persist_body(const GemmArgs g, int n_tiles_n, Se
         advance_b();
         asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
         asm volatile("s_barrier" ::: "memory");
+        // the carried scatter's piece (loaded before this step: covered by the wait above) goes out here, so
+        // that its stores have a whole step until the next wait, which has to see them acknowledged
+        if (COPY && store_copy) copy_store();
         group_reads(1, sa, sb, 1, false, CROSS, false, 0, sa_next, sb_next, 0, issue_a_one);
         advance_a();
         mfma_group(acc, 1);
@@ -563,8 +569,7 @@ __device__ __forceinline__ void persist_body(const GemmArgs g, int n_tiles_n, Se
             for (int kt = 0; kt + 2 < nk; ++kt) {
                 const bool copy_now = COPY && (kt % SC_PERIOD) == 0;
                 if (copy_now) copy_issue();
-                step(acc, T_{});
-                if (copy_now) copy_store();
+                step(acc, T_{}, copy_now);
             }
             set_a_sources(nxt);
             set_b_sources(nxt, nxt_n0);
