@@ -183,7 +183,7 @@ __device__ __forceinline__ void persist_body(const GemmArgs g, int n_tiles_n, Se
     // The kernel is bound by the matrix cores and leaves most of the HBM bandwidth unused, the row
     // scatter of the dispatch permutation is bound by HBM and leaves the matrix cores idle, and the
     // two are independent.  Every wavefront therefore moves SC_NU 1 KB pieces of token rows every
-    // SC_PERIOD-th K step: the pieces and their tokens' k positions are loaded just before a K step (so they are
+    // sc_period-th K step: the pieces and their tokens' k positions are loaded just before a K step (so they are
     // older than the step's four weight loads and have landed when the step's wait has passed) and
     // stored to the k rows right behind that wait and the barrier, in the middle of the step: vmcnt counts
     // stores too, so the next step's wait has to see them acknowledged, and from there they have a whole
@@ -198,12 +198,12 @@ __device__ __forceinline__ void persist_body(const GemmArgs g, int n_tiles_n, Se
     const int sc_stride = (int)gridDim.x * (THREADS / 64);
     int sc_u = (int)blockIdx.x * (THREADS / 64) + wave;                    // this wavefront's next piece
     typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-    // Measured on the 32768-token workload (k = 6): one piece every 4th step, all wavefronts at the same
-    // steps, adds 83 us to the 577 us projection for a 188 us scatter; four pieces every 16th step cost
-    // 30 us more than that, the wavefronts taking turns (some wavefront storing in every step) 40 us
-    // more, plain instead of non-temporal stores 20 us more.
+    // Measured on the 32768-token workload (k = 6) with the first version (stores after the step, a piece every
+    // 4th step): +83 us on the 577 us projection for a 188 us scatter; four pieces every 16th step cost 30 us more
+    // than that, the wavefronts taking turns (some wavefront storing in every step) 40 us more, plain instead of
+    // non-temporal stores 20 us more.
     constexpr int SC_NU = 1;                                               // pieces per copy event
-    constexpr int SC_PERIOD = 4 * SC_NU;                                   // K steps between copy events
+    int sc_period = 1, sc_countdown = 0;                                   // K steps between copy events (set below), steps to the next
     u32x4_t sc_data[SC_NU];
     int sc_pos_v[SC_NU], sc_q[SC_NU];
     int sc_pending = 0;                                                    // pieces loaded and not yet stored (uniform)
@@ -264,6 +264,15 @@ __device__ __forceinline__ void persist_body(const GemmArgs g, int n_tiles_n, Se
     }
 
     const int nk = g.K / BK;
+    // The pieces of this wavefront are spread evenly over the K steps it will run (every tile's steps but the
+    // last two), so that the scatter ends with the kernel instead of crowding its first part: measured on
+    // the 32768-token workload, a piece every 5th step (what this gives there) against every 4th 660 -> 645 us,
+    // every 3rd 680 us, every 2nd 687 us; every 6th would leave pieces for after the tile loop.
+    if (COPY && copy_on) {
+        const int my_tiles = (njobs - bslot + nblk - 1) / nblk;                           // > 0 here
+        const int my_pieces = sc_u < sc_units ? (sc_units - sc_u + sc_stride - 1) / sc_stride : 0;
+        sc_period = max(1, my_tiles * max(nk - 2, 0) / max(my_pieces, 1));
+    }
 
     // ---- load sources: a scalar base per operand (advancing along K) + a 32-bit byte offset per lane ----
     // One wavefront-wide load fills 1 KB of LDS = ROWS_PER_LOAD consecutive tile rows; lane l
@@ -567,7 +576,11 @@ __device__ __forceinline__ void persist_body(const GemmArgs g, int n_tiles_n, Se
                     for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
             fetch_entry(0, smem + a_con * A_BYTES, smem + B_BASE + b_con * B_BYTES, 0);
             for (int kt = 0; kt + 2 < nk; ++kt) {
-                const bool copy_now = COPY && (kt % SC_PERIOD) == 0;
+                bool copy_now = false;
+                if (COPY && --sc_countdown <= 0) {
+                    copy_now = true;
+                    sc_countdown = sc_period;
+                }
                 if (copy_now) copy_issue();
                 step(acc, T_{}, copy_now);
             }
