@@ -6,7 +6,9 @@
 //   1. topk_kernel   one wavefront per token: every lane ranks its logits against
 //                    all others by (logit desc, expert id asc) through scalar
 //                    broadcasts, ranks < k are the choices; softmax weights and a
-//                    histogram of the chosen experts per chunk of tokens;
+//                    histogram of the chosen experts per chunk of tokens
+//                    (topk_lanes_kernel, four lanes per token with sorted lists of the
+//                    best k, for more than 8192 tokens with k <= 8);
 //   2. route_scan    exclusive scan of the chunk histograms per expert -> the
 //                    number of earlier requests of each expert before each chunk
 //                    (the weighted round-robin counter of Section 4.3);
@@ -15,6 +17,8 @@
 //                    matching, and maps request number c to the candidate of the tier
 //                    Algorithm 4 selects whose cumulative polling-weight interval holds
 //                    c mod W.
+#include <type_traits>
+
 #include "common.h"
 #include "route_device.h"
 #include "wave_utils.h"
@@ -22,6 +26,8 @@
 namespace grace {
 
 constexpr int TOPK_THREADS = 512;  // 8 wavefronts per chunk, TPW tokens each (chunk = 8 * TPW tokens)
+
+constexpr int TOPK_LANES_MIN_T = 8193, TOPK_LANES_MIN_E = 32;  // from here on a few lanes per token (topk_lanes_kernel) where its conditions hold
 
 // One wavefront per token, VPL experts per lane (token_topk); a histogram of the chosen experts per
 // chunk of tokens feeds the request counter.
@@ -67,6 +73,131 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const float *__restr
     }
     __syncthreads();
     for (int i = tid; i < E; i += TOPK_THREADS) chunk_hist[(size_t)chunk * E + i] = hist[i];
+}
+
+// The same gate with four lanes per token, for batches large enough that the wavefront-per-token
+// kernel above is bound by its vector instructions (about 280 per token there, about 90 here): lane q
+// of a token scans experts [q * NV, q * NV + NV) in ascending order and keeps its K best as a sorted
+// list (insertion by strict "greater", so equal logits stay in ascending expert order); the lists of
+// the four lanes are merged pairwise the same way (the lower lane holds the lower expert ids and keeps
+// its entries ahead of equal ones), and lane 0 of the token writes the k <= K choices.  A workgroup
+// holds one chunk of tokens (blockDim = chunk tokens * 4).  Needs E % 4 == 0 and 16-byte aligned logits.
+constexpr int TOPK_LANES = 4;
+template <int K>
+struct BestList {
+    uint32_t key[K];  // ordered_bits of the logit, descending; 0 = empty
+    int id[K];
+    __device__ __forceinline__ void clear() {
+#pragma unroll
+        for (int j = 0; j < K; ++j) { key[j] = 0u; id[j] = 0; }
+    }
+    // (kx, ix) goes in front of the first entry it beats and behind those it ties with; the entries from
+    // there on move down one place.  All K comparisons are against the list as it was (it is sorted, so
+    // they are false up to the place of insertion and true from there on) and do not wait for each other.
+    __device__ __forceinline__ void insert(uint32_t kx, int ix) {
+        bool gt[K];
+#pragma unroll
+        for (int j = 0; j < K; ++j) gt[j] = kx > key[j];
+#pragma unroll
+        for (int j = K - 1; j >= 1; --j) {
+            const uint32_t in_k = gt[j - 1] ? key[j - 1] : kx;
+            const int in_i = gt[j - 1] ? id[j - 1] : ix;
+            key[j] = gt[j] ? in_k : key[j];
+            id[j] = gt[j] ? in_i : id[j];
+        }
+        key[0] = gt[0] ? kx : key[0];
+        id[0] = gt[0] ? ix : id[0];
+    }
+};
+
+template <int DPP_CTRL>
+__device__ __forceinline__ int dpp_move(int v) {
+    return __builtin_amdgcn_update_dpp(v, v, DPP_CTRL, 0xF, 0xF, false);
+}
+
+__device__ __forceinline__ float from_ordered_bits(uint32_t kb) {
+    return __uint_as_float((kb & 0x80000000u) ? (kb ^ 0x80000000u) : ~kb);
+}
+
+template <int NV, int K>
+__global__ __launch_bounds__(64 * TOPK_LANES) void topk_lanes_kernel(const float *__restrict__ logits, int T, int E, int k, int renorm,
+                                                            int32_t *__restrict__ topk_expert,
+                                                            float *__restrict__ topk_weight,
+                                                            int32_t *__restrict__ chunk_hist, int32_t *__restrict__ clear,
+                                                            int n_clear, int chunk_tokens) {
+    constexpr int L = TOPK_LANES;
+    static_assert(L == 4, "the merge and the broadcasts below are written for quads of lanes");
+    static_assert(NV % 4 == 0, "16-byte loads");
+    __shared__ int32_t hist[GRACE_MAX_EXPERTS];
+    const int tid = (int)threadIdx.x, nthr = (int)blockDim.x;
+    for (int i = tid; i < E; i += nthr) hist[i] = 0;
+    for (int64_t i = (int64_t)blockIdx.x * nthr + tid; i < n_clear; i += (int64_t)gridDim.x * nthr) clear[i] = 0;
+    __syncthreads();
+    const int chunk = (int)blockIdx.x;
+    const int q = tid % L;
+    const int t = chunk * chunk_tokens + tid / L;
+    const bool live = t < T;
+    // this lane's logits, all requested before any is used
+    float val[NV];
+    const int e0 = q * NV;
+#pragma unroll
+    for (int g = 0; g < NV / 4; ++g) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (live && e0 + 4 * g < E) v = *(const float4 *)(logits + (size_t)t * E + e0 + 4 * g);
+        val[4 * g] = v.x; val[4 * g + 1] = v.y; val[4 * g + 2] = v.z; val[4 * g + 3] = v.w;
+    }
+    BestList<K> best;
+    best.clear();
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        float x = val[i];
+        if (x == 0.0f) x = 0.0f;  // -0.0 and +0.0 compare equal: make them the same bits
+        val[i] = x;
+        best.insert((e0 + i < E) ? ordered_bits(x) : 0u, e0 + i);
+    }
+    // merge: after the step with distance s, lanes with q % (2 s) == 0 hold the best of 2 s lanes
+#pragma unroll
+    for (int s = 1; s < L; s <<= 1) {
+        uint32_t ok[K];
+        int oi[K];
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            ok[j] = (uint32_t)(s == 1 ? dpp_move<0xB1>((int)best.key[j]) : dpp_move<0x4E>((int)best.key[j]));
+            oi[j] = s == 1 ? dpp_move<0xB1>(best.id[j]) : dpp_move<0x4E>(best.id[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < K; ++j) best.insert(ok[j], oi[j]);
+    }
+    // softmax over all E logits, or over the k chosen ones; the maximum is the first choice
+    const float mx = from_ordered_bits(best.key[0]);  // valid in lane q == 0
+    float ex[K], sel = 0.0f;
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+        ex[j] = j < k ? expf(from_ordered_bits(best.key[j]) - mx) : 0.0f;
+        sel += ex[j];
+    }
+    float norm = sel;
+    if (!renorm) {  // uniform
+        const float mx_all = __builtin_bit_cast(float, dpp_move<0x00>(__builtin_bit_cast(int, mx)));  // the quad's lane 0
+        float part[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < NV; ++i) part[i & 3] += (e0 + i < E) ? expf(val[i] - mx_all) : 0.0f;
+        float den = (part[0] + part[1]) + (part[2] + part[3]);
+        den += __builtin_bit_cast(float, dpp_move<0xB1>(__builtin_bit_cast(int, den)));
+        den += __builtin_bit_cast(float, dpp_move<0x4E>(__builtin_bit_cast(int, den)));
+        norm = den;
+    }
+    if (live && q == 0) {
+#pragma unroll
+        for (int j = 0; j < K; ++j)
+            if (j < k) {
+                topk_expert[(size_t)t * k + j] = best.id[j];
+                topk_weight[(size_t)t * k + j] = ex[j] / norm;
+                atomicAdd(&hist[best.id[j]], 1);
+            }
+    }
+    __syncthreads();
+    for (int i = tid; i < E; i += nthr) chunk_hist[(size_t)chunk * E + i] = hist[i];
 }
 
 __global__ __launch_bounds__(SCAN_THREADS) void route_scan_kernel(const int32_t *__restrict__ hist,
@@ -220,6 +351,21 @@ int launch_topk(const float *logits, int T, int E, int k, int renorm, int32_t *t
                 int32_t *chunk_hist, int32_t *clear, int n_clear, hipStream_t st) {
     const int chunk_tokens = route_chunk_tokens(T);
     const int nchunks = (int)ceil_div(T, chunk_tokens);
+    if (T >= TOPK_LANES_MIN_T && E >= TOPK_LANES_MIN_E && k <= 8 && E % 4 == 0 && ((uintptr_t)logits & 15) == 0) {
+        const unsigned thr = (unsigned)(chunk_tokens * TOPK_LANES);
+        auto launch = [&](auto nv) {  // list length: the next of 2, 4, 6, 8 from k on
+            constexpr int NV = decltype(nv)::value;
+            auto *kern = k <= 2 ? topk_lanes_kernel<NV, 2> : k <= 4 ? topk_lanes_kernel<NV, 4> : k <= 6 ? topk_lanes_kernel<NV, 6>
+                                                                                                       : topk_lanes_kernel<NV, 8>;
+            kern<<<nchunks, thr, 0, st>>>(logits, T, E, k, renorm, topk_expert, topk_weight, chunk_hist, clear, n_clear,
+                                          chunk_tokens);
+        };
+        if (E <= 64) launch(std::integral_constant<int, 16>{});
+        else if (E <= 128) launch(std::integral_constant<int, 32>{});
+        else launch(std::integral_constant<int, 64>{});
+        GRACE_LAUNCH_CHECK("topk_lanes_kernel");
+        return GRACE_OK;
+    }
 #define GRACE_TOPK(VPL)                                                                                              \
     if (chunk_tokens == ROUTE_CHUNK_SMALL)                                                                           \
         topk_kernel<VPL, ROUTE_CHUNK_SMALL / (TOPK_THREADS / 64)><<<nchunks, TOPK_THREADS, 0, st>>>(                \

@@ -277,6 +277,32 @@ def test_route_wide_and_degenerate_expert_counts(E, k, T):
     check_route_permute(g, ref, wl, k)
 
 
+@pytest.mark.parametrize("E,k,T,renorm", [(64, 6, 8193, 1), (96, 8, 9001, 0), (128, 8, 8500, 1), (256, 5, 8200, 0),
+                                          (32, 2, 16500, 1), (64, 1, 17000, 0), (36, 3, 8300, 1), (200, 7, 8400, 1),
+                                          (64, 8, 20001, 0), (256, 8, 16385, 1), (32, 4, 33000, 0)])
+def test_route_large_batches_few_lanes_per_token(E, k, T, renorm):
+    """Batches above 8192 tokens with k <= 8 and E >= 32 a multiple of 4 take the top-k kernel that gives
+    each token four lanes: expert counts that leave lanes partly or wholly without experts, every
+    list length (k up to 2, 4, 6, 8), both softmax normalisations, ragged last chunks of 32 and of 64
+    tokens, ties everywhere (logits on a grid of halves, a row of zeros, a row mixing -0.0 and +0.0)."""
+    rng = np.random.default_rng(1000 * E + k)
+    R, N = 6, 3
+    hosts = [sorted(rng.choice(R, size=rng.integers(1, 4), replace=False).tolist()) for _ in range(E)]
+    inst_ptr = np.concatenate([[0], np.cumsum([len(h) for h in hosts])]).astype(np.int32)
+    pl = SimpleNamespace(E=E, R=R, N=N, rank_node=np.array([0, 0, 1, 1, 2, 2], np.int32),
+                         poll_weight=rng.integers(1, 9, size=R).astype(np.uint32), inst_ptr=inst_ptr,
+                         inst_rank=np.concatenate(hosts).astype(np.int32))
+    logits = np.round(rng.standard_normal((T, E)) * 2).astype(np.float32) / 2
+    logits[T // 2:] += (rng.standard_normal((T - T // 2, E)) * 1e-3).astype(np.float32)   # second half: few ties
+    logits[0, :] = 0.0
+    logits[1, ::2] = -0.0
+    logits[2, :] = -7.5
+    wl = SimpleNamespace(logits=logits, x=rng.standard_normal((T, 8)).astype(np.float32))
+    ref = oracle.route_permute(logits, pl, k, 4, renorm=renorm)
+    _, g = run_route_permute(wl, pl, k, 4, renorm=renorm)
+    check_route_permute(g, ref, wl, k)
+
+
 def test_empty_call_and_argument_errors():
     cfg = CONFIGS["tiny"]
     wl = make_workload(cfg)
