@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 namespace grace {
 
@@ -112,8 +113,37 @@ __device__ __forceinline__ void block_add_rows(const int32_t *__restrict__ m, in
     const bool vec = (s0 % 4 == 0) && (gs % 4 == 0);  // then every group start and o are multiples of four elements
     const int ngroups = (r1 - r0 + rg - 1) / rg;
     int32_t tot[4] = {0, 0, 0, 0}, lt[4] = {0, 0, 0, 0};
+    auto add = [&](const int32_t (&v)[4], int grp) {
+        const int rbase = r0 + grp * rg;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            tot[q] += v[q];
+            lt[q] += (rbase + row[q] < r_lt) ? v[q] : 0;
+        }
+    };
+    // every group but the last lies wholly below s1: batches of 8 and 4 unguarded 16-byte loads, all of a
+    // batch in flight before the first is used
+    auto batch = [&](int grp, auto nb) {
+        constexpr int NB = decltype(nb)::value;
+        uint4 x[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) x[b] = *(const uint4 *)(m + s0 + (int64_t)(grp + b) * gs + o);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int32_t v[4] = {(int32_t)x[b].x, (int32_t)x[b].y, (int32_t)x[b].z, (int32_t)x[b].w};
+            add(v, grp + b);
+        }
+    };
+    int grp = 0;
+    if (vec) {
+        for (; grp + 8 < ngroups; grp += 8) batch(grp, std::integral_constant<int, 8>{});
+        if (grp + 4 < ngroups) {
+            batch(grp, std::integral_constant<int, 4>{});
+            grp += 4;
+        }
+    }
 #pragma unroll 4
-    for (int grp = 0; grp < ngroups; ++grp) {
+    for (; grp < ngroups; ++grp) {
         const int64_t f = s0 + (int64_t)grp * gs + o;  // flat index of this thread's first element
         int32_t v[4] = {0, 0, 0, 0};
         if (vec && f + 3 < s1) {
@@ -124,12 +154,7 @@ __device__ __forceinline__ void block_add_rows(const int32_t *__restrict__ m, in
             for (int q = 0; q < 4; ++q)
                 if (on[q] && f + q < s1) v[q] = m[f + q];
         }
-        const int rbase = r0 + grp * rg;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            tot[q] += v[q];
-            lt[q] += (rbase + row[q] < r_lt) ? v[q] : 0;
-        }
+        add(v, grp);
     }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
