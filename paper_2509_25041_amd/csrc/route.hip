@@ -267,13 +267,25 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
     // prepared, so the picks below do not wait on chains of dependent global loads
     int e_first = (a0 + tid < a1) ? topk_expert[a0 + tid] : -1;
     // c_first = cand_ptr[0], n_cand = cand_ptr[E] - c_first: known to the host, so the staging loads
-    // below do not wait for them
+    // below do not wait for them.  The table entries stay in registers until the counters are prepared:
+    // their loads and those of the histogram rows are then in flight together (a kernel's first loads
+    // miss every cache level that is flushed between kernels, so each dependent round costs microseconds).
     const bool table_in_lds = n_cand <= PICK_LDS_CANDS;  // uniform
+    constexpr int CANDS_PER_THREAD = PICK_LDS_CANDS / PICK_THREADS;
+    static_assert(GRACE_MAX_EXPERTS + 1 <= PICK_THREADS && PICK_LDS_CANDS % PICK_THREADS == 0, "one offset, whole entries per thread");
+    int32_t st_ptr = 0, st_g[CANDS_PER_THREAD];
+    uint32_t st_cum[CANDS_PER_THREAD];
     if (table_in_lds) {
-        for (int i = tid; i <= E; i += PICK_THREADS) s_ptr[i] = cand_ptr[i] - c_first;
-        for (int i = tid; i < n_cand; i += PICK_THREADS) {
-            s_g[i] = cand_g[c_first + i];
-            s_cum[i] = cand_cum[c_first + i];
+        if (tid <= E) st_ptr = cand_ptr[tid];
+#pragma unroll
+        for (int q = 0; q < CANDS_PER_THREAD; ++q) {
+            const int i = tid + q * PICK_THREADS;
+            st_g[q] = 0;
+            st_cum[q] = 0u;
+            if (i < n_cand) {
+                st_g[q] = cand_g[c_first + i];
+                st_cum[q] = cand_cum[c_first + i];
+            }
         }
     }
     if (FOLD) {
@@ -290,6 +302,17 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(const int32_t *__res
         }
     } else {
         for (int e = tid; e < E; e += PICK_THREADS) cnt[e] = chunk_counts[(size_t)row0 * E + e];
+    }
+    if (table_in_lds) {
+        if (tid <= E) s_ptr[tid] = st_ptr - c_first;
+#pragma unroll
+        for (int q = 0; q < CANDS_PER_THREAD; ++q) {
+            const int i = tid + q * PICK_THREADS;
+            if (i < n_cand) {
+                s_g[i] = st_g[q];
+                s_cum[i] = st_cum[q];
+            }
+        }
     }
     const int32_t *t_ptr = table_in_lds ? s_ptr : cand_ptr;
     const int32_t *t_g = table_in_lds ? s_g : cand_g;
