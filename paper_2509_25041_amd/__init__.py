@@ -29,6 +29,8 @@ from .binding import (  # noqa: F401
     grace_route_permute_static,
     grace_send_lists,
     grace_shared_ffn,
+    grace_shared_ffn_down,
+    grace_shared_ffn_up,
     grace_shared_ffn_up_scatter,
     grace_table_validate,
     grace_workspace_bytes,

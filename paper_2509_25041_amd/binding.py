@@ -376,6 +376,27 @@ def grace_shared_ffn(x: torch.Tensor, w_gate: torch.Tensor, w_up: torch.Tensor, 
     return y_shared
 
 
+def grace_shared_ffn_up(x: torch.Tensor, w_gate: torch.Tensor, w_up: torch.Tensor, ws: torch.Tensor) -> None:
+    """First launch of grace_shared_ffn: the hidden activation of all T rows into ws; see grace_moe.h."""
+    T, d = x.shape
+    n_shared, f, _ = w_gate.shape
+    if tuple(w_up.shape) != (n_shared, f, d):
+        raise ValueError("weights must be w_gate/w_up [n,f,d]")
+    _check(load_library().grace_shared_ffn_up(_dp(x), T, d, f, n_shared, _dtype_code(x), _dp(w_gate), _dp(w_up), _dp(ws),
+                                              _stream()))
+
+
+def grace_shared_ffn_down(w_down: torch.Tensor, ws: torch.Tensor, T: int,
+                          y_shared: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Second launch of grace_shared_ffn: reads the hidden activation grace_shared_ffn_up left in ws; see grace_moe.h."""
+    n_shared, d, f = w_down.shape
+    if y_shared is None:
+        y_shared = torch.empty((T, d), dtype=w_down.dtype, device=w_down.device)
+    _check(load_library().grace_shared_ffn_down(T, d, f, n_shared, _dtype_code(w_down), _dp(w_down), _dp(y_shared), _dp(ws),
+                                                _stream()))
+    return y_shared
+
+
 def grace_permute_rows(x: torch.Tensor, perm_pos: torch.Tensor, k: int, xp: Optional[torch.Tensor] = None) -> torch.Tensor:
     """The row movement of grace_permute alone: xp[perm_pos[t*k+j]] = x[t]; see grace_moe.h."""
     T, d = x.shape

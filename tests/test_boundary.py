@@ -29,6 +29,20 @@ def test_library_exports_every_declared_symbol():
     assert os.path.dirname(grace.library_path()).endswith("paper_2509_25041_amd")
 
 
+def test_binding_has_the_entry_points_under_their_own_names():
+    """Every exported call is reachable from Python under the C name (functions of the binding, re-exported
+    by the package), the table's calls as methods of GraceTable."""
+    methods = {"grace_table_create": "__init__", "grace_table_destroy": "destroy", "grace_table_info": "__init__",
+               "grace_table_instances": "instances", "grace_table_local_experts": "local_experts",
+               "grace_table_set_fold_limits": "set_fold_limits"}
+    for n in binding.EXPORTS:
+        if n in methods:
+            assert callable(getattr(grace.GraceTable, methods[n]))
+        else:
+            assert callable(getattr(binding, n)), n
+            assert getattr(grace, n) is getattr(binding, n), n
+
+
 def test_valid_tables_pass_validation():
     for cfg in CONFIGS.values():
         pl = make_workload(cfg, T=256).placement

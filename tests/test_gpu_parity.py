@@ -593,13 +593,16 @@ def test_shared_up_with_row_scatter_equals_the_two_calls(T, d, f, n_shared, k, d
     xp_a = torch.full((T * k, d), 7.0, dtype=tdt, device="cuda")
     xp_b = torch.full((T * k, d), 7.0, dtype=tdt, device="cuda")
     grace.grace_shared_ffn_up_scatter(x, wg, wu, ws_a, pos, k, xp_a)
-    lib = grace.load_library()
-    import ctypes as C
-    from paper_2509_25041_amd.binding import _check, _dp, _dtype_code, _stream
-    _check(lib.grace_shared_ffn_up(_dp(x), T, d, f, n_shared, _dtype_code(x), _dp(wg), _dp(wu), _dp(ws_b), _stream()))
+    grace.grace_shared_ffn_up(x, wg, wu, ws_b)
     grace.grace_permute_rows(x, pos, k, xp_b)
     torch.cuda.synchronize()
     assert torch.equal(ws_a, ws_b)                                   # the hidden activation, bit for bit
+    # the two launches of the shared FFN as separate calls against the single call
+    wd = torch.from_numpy((0.05 * rng.standard_normal((n_shared, d, f))).astype(np.float32)).cuda().to(tdt)
+    ys_two = grace.grace_shared_ffn_down(wd, ws_b, T)
+    ys_one = grace.grace_shared_ffn(x, wg, wu, wd)
+    torch.cuda.synchronize()
+    assert torch.equal(ys_two.view(torch.uint8), ys_one.view(torch.uint8))
     assert torch.equal(xp_a.view(torch.uint8), xp_b.view(torch.uint8))
     # rows against the definition: xp[p] = x[a // k] where perm_pos[a] = p; dropped positions keep their old contents
     got, xh = host(xp_a), host(x)
