@@ -271,6 +271,8 @@ def test_route_wide_and_degenerate_expert_counts(E, k, T):
     logits = np.round(rng.standard_normal((T, E)) * 2).astype(np.float32) / 2      # heavy ties
     logits[0, :] = 0.0
     logits[1, ::2] = -0.0
+    logits[2, ::3] = -np.inf          # masked experts: never ahead of a finite logit, weight exactly 0
+    logits[3, 1:] = -np.inf           # one finite logit: the other choices in expert order, weight 0
     wl = SimpleNamespace(logits=logits, x=rng.standard_normal((T, 8)).astype(np.float32))
     ref = oracle.route_permute(logits, pl, k, 2)
     _, g = run_route_permute(wl, pl, k, 2)
@@ -297,6 +299,9 @@ def test_route_large_batches_few_lanes_per_token(E, k, T, renorm):
     logits[0, :] = 0.0
     logits[1, ::2] = -0.0
     logits[2, :] = -7.5
+    logits[3, ::3] = -np.inf          # masked experts: never ahead of a finite logit, weight exactly 0
+    logits[4, 5:] = -np.inf           # fewer finite logits than k <= 8 may ask for: the rest in expert order, weight 0
+    logits[T - 1, 1:] = -np.inf
     wl = SimpleNamespace(logits=logits, x=rng.standard_normal((T, 8)).astype(np.float32))
     ref = oracle.route_permute(logits, pl, k, 4, renorm=renorm)
     _, g = run_route_permute(wl, pl, k, 4, renorm=renorm)
