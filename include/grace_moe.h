@@ -133,7 +133,9 @@ size_t grace_workspace_bytes(int32_t T, int32_t E, int32_t k, int32_t I, int32_t
  * Gating (Section 3: every token activates k experts): the k largest logits of
  * a token, in descending order, equal logits to the lower expert id; gate
  * weight = softmax over all E logits, divided by the sum over the k chosen when
- * renorm != 0.
+ * renorm != 0.  -0.0 equals +0.0; a logit of -infinity masks an expert: it
+ * ranks behind every finite logit and its weight is exactly 0 (a token needs
+ * at least one finite logit; NaN and +infinity are not defined inputs).
  * Replica pick (Section 4.3; Algorithm 4 with Algorithm 3 inside a tier): all
  * T tokens reside on local_rank.  For each assignment, in order of a, the c-th
  * request for expert e (c starts at rr_in[e]) goes to
